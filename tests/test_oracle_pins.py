@@ -1,0 +1,377 @@
+"""CPU pins of the oracle against what the paper and the mathematics fix.
+
+Each test names the passage it pins.  None of them re-types the oracle's own
+formula: they use brute force, closed forms, hand-worked cases, invariants or a
+library routine (numpy / torch in fp64).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import binattn_oracle as orc
+from tests.helpers import bf16_bits, bits_to_f64, f32_to_bits
+
+
+def randn_bits(shape, seed, scale=1.0):
+    g = torch.Generator().manual_seed(seed)
+    return bf16_bits(torch.randn(*shape, generator=g) * scale)
+
+
+# --------------------------------------------------------------------------
+# sign(.)  (Sec. 3: +1 on non-negative values, -1 otherwise)
+# --------------------------------------------------------------------------
+def test_sign_hand_cases():
+    #            +0      -0      +tiny   -tiny   +inf    -inf    NaN     -NaN    1.0     -1.0
+    bits = np.array([0x0000, 0x8000, 0x0001, 0x8001, 0x7F80, 0xFF80, 0x7FC0, 0xFFC0, 0x3F80, 0xBF80],
+                    dtype=np.uint16)
+    want = np.array([1, 1, 1, -1, 1, -1, -1, -1, 1, -1], dtype=np.int8)
+    assert np.array_equal(orc.sign_pm1(bits), want)
+
+
+def test_sign_pack_layout_hand_cases():
+    d = 40  # two words, 24 padding bits
+    x = -np.ones((5, d), dtype=np.float32)
+    x[0, 0] = 1.0            # word 0 bit 0
+    x[1, 31] = 1.0           # word 0 bit 31
+    x[2, 32] = 1.0           # word 1 bit 0
+    x[3, 39] = 1.0           # word 1 bit 7
+    x[4, :] = 1.0            # all real channels set, padding stays 0
+    w = orc.sign_pack(f32_to_bits(x))
+    want = np.array([[1, 0], [0x80000000, 0], [0, 1], [0, 0x80], [0xFFFFFFFF, 0xFF]], dtype=np.uint32)
+    assert w.dtype == np.uint32 and np.array_equal(w, want)
+
+
+def test_sign_pack_agrees_with_pm1_and_numpy():
+    x = randn_bits((33, 72), 11)
+    w = orc.sign_pack(x)
+    s = orc.sign_pm1(x)
+    vals = bits_to_f64(x)
+    assert np.array_equal(s, np.where(vals >= 0, 1, -1).astype(np.int8))
+    # unpack with numpy and compare
+    bits = ((w[:, :, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(33, -1)
+    assert np.array_equal(bits[:, :72], (s > 0).astype(np.uint32))
+    assert not bits[:, 72:].any()
+
+
+@pytest.mark.parametrize("alpha", [0.5, 3.0, 2.0 ** -10, 100.0, 0.37])
+def test_sign_is_invariant_under_positive_scaling(alpha):
+    # Supplementary Sec. A (last step of the proof): sign is scale invariant
+    # for strictly positive scales.
+    g = torch.Generator().manual_seed(5)
+    x = torch.randn(64, 64, generator=g)
+    a = orc.sign_pack(bf16_bits(x))
+    b = orc.sign_pack(bf16_bits(x.to(torch.bfloat16).float() * alpha))
+    assert np.array_equal(a, b)
+
+
+# --------------------------------------------------------------------------
+# +-1 inner product and the Hamming identity (Sec. 4.1)
+# --------------------------------------------------------------------------
+def test_hamming_identity_brute_force_all_patterns_d8():
+    d = 8
+    pats = np.array([[1.0 if (p >> c) & 1 else -1.0 for c in range(d)] for p in range(256)],
+                    dtype=np.float32)
+    xb = f32_to_bits(pats)
+    lit = orc.logits_literal(xb, xb)
+    ham = orc.logits_hamming(orc.sign_pack(xb), orc.sign_pack(xb), d)
+    # brute force in pure Python: count agreeing minus disagreeing positions
+    for i in range(0, 256, 17):
+        for j in range(256):
+            agree = sum(1 for c in range(d) if ((i >> c) & 1) == ((j >> c) & 1))
+            assert lit[i, j] == agree - (d - agree)
+    assert np.array_equal(lit, ham)
+    # d - 2 * popcount(i xor j) for every pair
+    ii, jj = np.meshgrid(np.arange(256), np.arange(256), indexing="ij")
+    pc = np.array([bin(v).count("1") for v in range(256)])[ii ^ jj]
+    assert np.array_equal(lit, d - 2 * pc)
+
+
+@pytest.mark.parametrize("d", [8, 64, 72, 128])
+def test_logits_literal_vs_hamming_vs_library_matmul(d):
+    N = 77
+    q, k = randn_bits((N, d), 100 + d), randn_bits((N, d), 200 + d)
+    lit = orc.logits_literal(q, k)
+    ham = orc.logits_hamming(orc.sign_pack(q), orc.sign_pack(k), d)
+    sq = np.where(bits_to_f64(q) >= 0, 1.0, -1.0)
+    sk = np.where(bits_to_f64(k) >= 0, 1.0, -1.0)
+    lib = (sq @ sk.T).astype(np.int64)          # library contraction, fp64 exact
+    assert np.array_equal(lit, ham)
+    assert np.array_equal(lit.astype(np.int64), lib)
+    assert np.all((lit - d) % 2 == 0) and np.all(np.abs(lit) <= d)
+    # transposition would show here: logits(q, k) is the transpose of logits(k, q)
+    assert np.array_equal(orc.logits_literal(k, q), lit.T)
+    assert not np.array_equal(lit, lit.T)
+
+
+def test_logits_self_and_negated():
+    d, N = 72, 9
+    q = randn_bits((N, d), 3)
+    neg = q ^ np.uint16(0x8000)
+    assert np.all(np.diag(orc.logits_literal(q, q)) == d)
+    assert np.all(np.diag(orc.logits_literal(q, neg)) == -d)
+    rows = np.array([4, 0, 8])
+    assert np.array_equal(orc.logits_literal(q, neg, rows=rows), orc.logits_literal(q, neg)[rows])
+
+
+@pytest.mark.parametrize("rho", [0.0, 0.3, -0.3, 0.7, -0.7, 0.95, -0.95])
+def test_theorem1_arcsine_law(rho):
+    # Theorem 1: E[sign(q) sign(k)] = (2/pi) arcsin(correlation) for zero-mean
+    # jointly Gaussian q, k.  Channel c of token i of q and k are correlated.
+    N, d = 2048, 64
+    g = torch.Generator().manual_seed(42)
+    z1 = torch.randn(N, d, generator=g)
+    z2 = torch.randn(N, d, generator=g)
+    q = z1 * 1.7                                  # arbitrary positive scales
+    k = (rho * z1 + math.sqrt(1 - rho * rho) * z2) * 0.4
+    I = orc.logits_literal(bf16_bits(q), bf16_bits(k))
+    est = np.diag(I).astype(np.float64).mean() / d
+    want = 2.0 / math.pi * math.asin(rho)
+    assert abs(est - want) < 4.0 / math.sqrt(N * d)
+    off = (I.sum() - np.trace(I)) / (N * (N - 1)) / d   # independent tokens: mean 0
+    assert abs(off) < 4.0 / math.sqrt(N * (N - 1) * d) + 1e-4
+
+
+# --------------------------------------------------------------------------
+# mu (Eq. 5 text)
+# --------------------------------------------------------------------------
+def test_mu_hand_and_scaling():
+    x = f32_to_bits(np.array([[1.0, -2.0], [3.0, -4.0]], dtype=np.float32))
+    assert orc.abs_mean(x) == 2.5
+    y = randn_bits((50, 64), 8)
+    y2 = f32_to_bits(bits_to_f64(y).astype(np.float32) * 4.0)
+    assert orc.abs_mean(y2) == 4.0 * orc.abs_mean(y)
+    assert orc.abs_mean(y) == pytest.approx(np.abs(bits_to_f64(y)).mean(), rel=1e-13)
+
+
+def test_mu_closed_form_standard_normal():
+    # E|x| = sqrt(2/pi) for x ~ N(0,1): the optimal binary scale of Sec. 3.
+    N, d = 4096, 64
+    mu = orc.abs_mean(randn_bits((N, d), 77))
+    se = math.sqrt(1 - 2 / math.pi) / math.sqrt(N * d)
+    assert abs(mu - math.sqrt(2 / math.pi)) < 5 * se + 2e-4
+
+
+# --------------------------------------------------------------------------
+# V quantisation (Eq. 7)
+# --------------------------------------------------------------------------
+def test_quant_v_hand_cases_ties_to_even_and_clamp():
+    col0 = [0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 127.0, -127.0, 3.25, 3.75]   # delta = 1
+    col1 = [0.0] * 10                                                     # delta = 1 (all zero)
+    col2 = [254.0, -254.0, 1.0, 3.0, -3.0, 5.0, 100.0, 0.0, 2.0, -1.0]    # delta = 2
+    v = f32_to_bits(np.array([col0, col1, col2], dtype=np.float32).T)
+    vq, delta = orc.quant_v(v)
+    assert delta.tolist() == [1.0, 1.0, 2.0]
+    assert vq[:, 0].tolist() == [0, 2, 2, 0, -2, -2, 127, -127, 3, 4]
+    assert vq[:, 1].tolist() == [0] * 10
+    #            254/2 -254/2  .5->0  1.5->2  -1.5->-2  2.5->2  50  0  1  -.5->0
+    assert vq[:, 2].tolist() == [127, -127, 0, 2, -2, 2, 50, 0, 1, 0]
+
+
+def test_quant_v_invariants_and_library_check():
+    N, d = 300, 72
+    g = torch.Generator().manual_seed(9)
+    v = torch.randn(N, d, generator=g) * torch.rand(1, d, generator=g) * 5
+    vb = bf16_bits(v)
+    vq, delta = orc.quant_v(vb)
+    vals = bits_to_f64(vb)
+    amax = np.abs(vals).max(axis=0)
+    assert np.array_equal(delta, (amax.astype(np.float32) / np.float32(127.0)))
+    assert np.abs(vq.astype(int)).max() <= 127
+    assert np.all(np.abs(vq.astype(int)).max(axis=0) == 127)
+    assert np.all(np.abs(vals - delta.astype(np.float64) * vq) <= delta / 2 * (1 + 1e-4))  # fp32 quotient rounding
+    lib = np.clip(np.rint(vals.astype(np.float32) / delta[None, :]), -127, 127).astype(np.int8)
+    assert np.array_equal(vq, lib)
+
+
+# --------------------------------------------------------------------------
+# softmax, logits with scale and bias (Eq. 1, Eq. 6)
+# --------------------------------------------------------------------------
+def _head(N, d, seed, bias_std=0.5, bias_f32=True):
+    g = torch.Generator().manual_seed(seed)
+    q = bf16_bits(torch.randn(N, d, generator=g))
+    k = bf16_bits(torch.randn(N, d, generator=g) + 0.3)
+    v = bf16_bits(torch.randn(N, d, generator=g) * 2)
+    b = torch.randn(N, N, generator=g) * bias_std
+    bias = b.numpy().astype(np.float32) if bias_f32 else bf16_bits(b)
+    return q, k, v, bias
+
+
+def test_softmax_rows_sum_to_one_and_max_is_one():
+    N, d = 61, 64
+    q, k, v, bias = _head(N, d, 1)
+    vq, delta = orc.quant_v(v)
+    o = orc.attention_rows(q, k, v, bias, 0.125, 0.8, 0.9, vq, delta, want=("P_hat", "l", "m", "S"))
+    P = o["P_hat"] / o["l"][:, None]
+    assert np.allclose(P.sum(axis=1), 1.0, atol=1e-12)
+    assert np.all(o["P_hat"] > 0) and np.all(o["P_hat"] <= 1.0)
+    assert np.all(o["P_hat"].max(axis=1) == 1.0)
+    assert np.array_equal(o["m"], o["S"].max(axis=1))
+
+
+def test_logits_S_match_eq6_with_library_contraction():
+    N, d = 40, 72
+    q, k, v, bias = _head(N, d, 2, bias_f32=False)
+    vq, delta = orc.quant_v(v)
+    scale, mq, mk = 1 / math.sqrt(d), 0.81, 0.77
+    S = orc.attention_rows(q, k, v, bias, scale, mq, mk, vq, delta, want=("S",))["S"]
+    sq = np.where(bits_to_f64(q) >= 0, 1.0, -1.0)
+    sk = np.where(bits_to_f64(k) >= 0, 1.0, -1.0)
+    want = mq * mk * (sq @ sk.T) / math.sqrt(d) + bits_to_f64(bias)
+    assert np.allclose(S, want, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("N,d,bias_f32", [(50, 64, True), (197, 64, False), (33, 72, False), (8, 128, True)])
+def test_unquantised_output_matches_library_softmax_attention(N, d, bias_f32):
+    # Eq. 1 with the logits of Eq. 6 through torch's fp64 softmax and matmul.
+    q, k, v, bias = _head(N, d, 20 + N, bias_f32=bias_f32)
+    vq, delta = orc.quant_v(v)
+    scale, mq, mk = 1 / math.sqrt(d), orc.abs_mean(q), orc.abs_mean(k)
+    O1 = orc.attention_rows(q, k, v, bias, scale, mq, mk, vq, delta, want=("O1",))["O1"]
+    tq = torch.tensor(np.where(bits_to_f64(q) >= 0, 1.0, -1.0))
+    tk = torch.tensor(np.where(bits_to_f64(k) >= 0, 1.0, -1.0))
+    tb = torch.tensor(bias.astype(np.float64) if bias_f32 else bits_to_f64(bias))
+    logits = (tq @ tk.T) * (scale * mq * mk) + tb
+    want = torch.softmax(logits, dim=-1) @ torch.tensor(bits_to_f64(v))
+    assert np.allclose(O1, want.numpy(), rtol=0, atol=1e-10)
+    # no-bias variant as well (drops the bias term only)
+    O1nb = orc.attention_rows(q, k, v, None, scale, mq, mk, vq, delta, want=("O1",))["O1"]
+    want_nb = torch.softmax((tq @ tk.T) * (scale * mq * mk), dim=-1) @ torch.tensor(bits_to_f64(v))
+    assert np.allclose(O1nb, want_nb.numpy(), rtol=0, atol=1e-10)
+    assert not np.allclose(O1, O1nb, atol=1e-4)
+
+
+def test_softmax_shift_invariance_per_row():
+    N, d = 45, 64
+    q, k, v, bias = _head(N, d, 4)
+    vq, delta = orc.quant_v(v)
+    shifted = (bias.astype(np.float64) + np.linspace(-3, 3, N)[:, None]).astype(np.float32)
+    a = orc.attention_rows(q, k, v, bias, 0.125, 0.8, 0.8, vq, delta, want=("O1",))["O1"]
+    b = orc.attention_rows(q, k, v, shifted, 0.125, 0.8, 0.8, vq, delta, want=("O1",))["O1"]
+    assert np.allclose(a, b, atol=1e-5)      # fp32 bias rounding only
+
+
+# --------------------------------------------------------------------------
+# quantised output O2 (Eq. 7 + Alg. 1 final line): special cases
+# --------------------------------------------------------------------------
+def test_O2_single_token_is_dequantised_value():
+    d = 64
+    q, k, v = randn_bits((1, d), 1), randn_bits((1, d), 2), randn_bits((1, d), 3)
+    vq, delta = orc.quant_v(v)
+    o = orc.attention_rows(q, k, v, None, 0.125, 0.8, 0.8, vq, delta, want=("O2", "P_code", "l"))
+    assert o["P_code"].tolist() == [[255]] and o["l"].tolist() == [1.0]
+    assert np.array_equal(o["O2"][0], delta.astype(np.float64) * vq[0])
+    assert np.all(np.abs(vq[0]) == 127)   # N = 1: every channel sits at its own absmax
+
+
+def test_O2_uniform_attention_is_column_mean_of_dequantised_V():
+    N, d = 37, 72
+    q, k, v, _ = _head(N, d, 6)
+    vq, delta = orc.quant_v(v)
+    # scale = 0 and no bias: every logit is 0, every code is 255, l = N
+    o = orc.attention_rows(q, k, v, None, 0.0, 0.8, 0.8, vq, delta, want=("O2", "P_code", "l", "O1"))
+    assert np.all(o["P_code"] == 255) and np.all(o["l"] == N)
+    want = delta.astype(np.float64) * vq.astype(np.float64).sum(axis=0) / N
+    assert np.allclose(o["O2"], want[None, :], rtol=1e-14, atol=0)
+    assert np.allclose(o["O1"], bits_to_f64(v).mean(axis=0)[None, :], atol=1e-12)
+    # identical keys and no bias give the same uniform rows for any scale
+    k_same = np.repeat(k[:1], N, axis=0)
+    o2 = orc.attention_rows(q, k_same, v, None, 0.125, 0.8, 0.8, vq, delta, want=("O2",))
+    assert np.allclose(o2["O2"], want[None, :], rtol=1e-14, atol=0)
+
+
+def test_O2_one_dominant_key_selects_that_value_row():
+    N, d = 29, 64
+    q, k, v, _ = _head(N, d, 7)
+    vq, delta = orc.quant_v(v)
+    bias = np.zeros((N, N), dtype=np.float32)
+    star = (np.arange(N) * 5 + 3) % N
+    bias[np.arange(N), star] = 50.0
+    o = orc.attention_rows(q, k, v, bias, 0.125, 0.8, 0.8, vq, delta, want=("O2", "P_code"))
+    codes = o["P_code"]
+    assert np.all(codes[np.arange(N), star] == 255) and codes.sum() == 255 * N
+    want = delta.astype(np.float64)[None, :] * vq[star].astype(np.float64)
+    assert np.allclose(o["O2"], want, rtol=1e-12, atol=0)
+
+
+def test_P_codes_hand_values_scale_255_round_to_nearest():
+    # scale = 0 so the logits are the fp32 bias alone; key 0 has bias 0 (the max).
+    targets = [1.0, 0.6, 0.35, 0.27, 0.123, 0.2, 0.25, 0.001, 0.0021]
+    # 255 * p:  255  153  89.25 68.85 31.365 51  63.75 0.255 0.5355
+    want = [255, 153, 89, 69, 31, 51, 64, 0, 1]
+    N, d = len(targets), 8
+    q, k, v = randn_bits((N, d), 1), randn_bits((N, d), 2), randn_bits((N, d), 3)
+    vq, delta = orc.quant_v(v)
+    bias = np.tile(np.log(np.array(targets, dtype=np.float64)).astype(np.float32), (N, 1))
+    o = orc.attention_rows(q, k, v, bias, 0.0, 1.0, 1.0, vq, delta, want=("P_code", "l", "O2"))
+    assert o["P_code"][0].tolist() == want
+    assert o["l"][0] == pytest.approx(sum(targets), rel=1e-6)
+    # aggregation with those codes, by hand in exact integers
+    acc = (np.array(want, dtype=np.int64)[:, None] * vq.astype(np.int64)).sum(axis=0)
+    assert np.allclose(o["O2"][0], delta.astype(np.float64) * acc / (255.0 * o["l"][0]), rtol=1e-14)
+
+
+def test_O2_within_quantisation_bound_of_O1():
+    N, d = 197, 64
+    q, k, v, bias = _head(N, d, 12, bias_std=0.02, bias_f32=False)
+    vq, delta = orc.quant_v(v)
+    mq, mk = orc.abs_mean(q), orc.abs_mean(k)
+    o = orc.attention_rows(q, k, v, bias, 0.125, mq, mk, vq, delta, want=("O2", "O1", "l"))
+    dq = delta.astype(np.float64)
+    # |v - delta*code| <= delta/2 under weights summing to 1, plus <= 0.5 code units per key
+    bound = dq[None, :] / 2 + N * 0.5 * np.abs(dq * vq).max(axis=0)[None, :] / (255.0 * o["l"][:, None])
+    err = np.abs(o["O2"] - o["O1"])
+    assert np.all(err <= bound)
+    assert err.max() > 0 and err.max() < 2e-2     # and it is a real, small quantisation error
+
+
+# --------------------------------------------------------------------------
+# Alg. 1 (blocked, running max) against the definition
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("Bv", [1, 7, 64, 1000])
+def test_algorithm1_unquantised_is_block_size_independent(Bv):
+    N, d = 150, 72
+    q, k, v, bias = _head(N, d, 30, bias_std=1.0)
+    vq, delta = orc.quant_v(v)
+    args = (q, k, v, bias, 1 / math.sqrt(d), 0.8, 0.75, vq, delta)
+    O1 = orc.attention_rows(*args, want=("O1",))["O1"]
+    A = orc.algorithm1_rows(*args, Bv=Bv, quantise=False)
+    assert np.allclose(A, O1, rtol=0, atol=1e-12)
+
+
+def test_algorithm1_quantised_single_block_equals_definition_and_blocks_stay_close():
+    N, d = 150, 64
+    q, k, v, bias = _head(N, d, 31, bias_std=0.3)
+    vq, delta = orc.quant_v(v)
+    args = (q, k, v, bias, 0.125, 0.8, 0.8, vq, delta)
+    O2 = orc.attention_rows(*args, want=("O2",))["O2"]
+    one = orc.algorithm1_rows(*args, Bv=N, quantise=True)
+    assert np.allclose(one, O2, rtol=1e-13, atol=1e-15)
+    for Bv in (16, 32, 128):
+        blk = orc.algorithm1_rows(*args, Bv=Bv, quantise=True)
+        assert np.all(np.abs(blk - O2) <= 1e-2 + 2e-2 * np.abs(O2))
+    rows = np.array([149, 3, 77])
+    sub = orc.algorithm1_rows(*args, Bv=32, quantise=True, rows=rows)
+    assert np.array_equal(sub, orc.algorithm1_rows(*args, Bv=32, quantise=True)[rows])
+
+
+# --------------------------------------------------------------------------
+# whole-layer driver
+# --------------------------------------------------------------------------
+def test_forward_driver_composes_heads_and_shares_bias_over_batch():
+    B, H, N, d = 2, 3, 21, 64
+    g = torch.Generator().manual_seed(3)
+    q = bf16_bits(torch.randn(B, H, N, d, generator=g))
+    k = bf16_bits(torch.randn(B, H, N, d, generator=g))
+    v = bf16_bits(torch.randn(B, H, N, d, generator=g))
+    bias = bf16_bits(torch.randn(H, N, N, generator=g) * 0.1)
+    res = orc.forward(q, k, v, bias, 0.125)
+    b, h = 1, 2
+    vq, delta = orc.quant_v(v[b, h])
+    one = orc.attention_rows(q[b, h], k[b, h], v[b, h], bias[h], 0.125, orc.abs_mean(q[b, h]),
+                             orc.abs_mean(k[b, h]), vq, delta)
+    assert np.array_equal(res["O2"][b, h], one["O2"]) and np.array_equal(res["O1"][b, h], one["O1"])
+    assert res["mu_q"][b, h] == orc.abs_mean(q[b, h])
+    nomu = orc.forward(q, k, v, bias, 0.125, use_mu=False, heads=[(0, 0)])
+    assert nomu["mu_q"][0, 0] == 1.0 and not np.allclose(nomu["O2"][0, 0], res["O2"][0, 0])
