@@ -1,0 +1,161 @@
+/*
+ * binattn -- BinaryAttention forward for AMD MI355X (gfx950), C ABI.
+ *
+ * The library computes one attention layer the way the paper's Alg. 1 does:
+ *   phi:  Q, K -> sign bits + scales mu_q, mu_k              (Eq. 5)
+ *   psi:  V    -> signed 8-bit codes + per-channel delta_v   (Eq. 7)
+ *   S_ij  = scale * mu_q * mu_k * (s_i . t_j) + b_ij         (Eq. 6)
+ *   online softmax over key blocks, P quantised to unsigned 8 bits with
+ *   scale 1/255 relative to the running row maximum, integer P~.V~ with
+ *   32-bit accumulation, O = O / (255 l) * delta_v           (Alg. 1)
+ * with (B, H) independent problems of N tokens and head dimension d.
+ *
+ * Conventions for every entry point
+ *  - All data pointers are DEVICE pointers owned by the caller (the library
+ *    never allocates, frees or synchronises); `stream` is a hipStream_t passed
+ *    as void* (NULL = the default stream).  Work is enqueued asynchronously.
+ *  - Stride arrays hold ELEMENT strides for the (batch, head, row) axes; the
+ *    innermost (channel / column) stride is always 1.
+ *  - Return value 0 on success, a negative BINATTN_ERR_* otherwise.  All
+ *    arguments are validated before anything is launched, so a failing call
+ *    leaves every output untouched.  Inputs are never modified.
+ *  - Supported shapes: B, H, N >= 1 with B*H < 2^31 / 128 and N <= 2^24;
+ *    d a multiple of 8 with 8 <= d <= 128.
+ *  - Q, K, V and the output are bf16; their base pointers must be 16-byte
+ *    aligned and every stride a multiple of 8 elements.
+ *  - Calls on one stream are ordered; the entry points keep no global mutable
+ *    state, so calls on different streams with disjoint buffers are
+ *    independent.
+ */
+#ifndef BINATTN_H
+#define BINATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    BINATTN_OK = 0,
+    BINATTN_ERR_NULL = -1,      /* a required pointer is NULL                      */
+    BINATTN_ERR_SHAPE = -2,     /* B, H, N or d outside the supported range        */
+    BINATTN_ERR_STRIDE = -3,    /* a stride is negative, too small or misaligned   */
+    BINATTN_ERR_ALIGN = -4,     /* a base pointer is not aligned as required       */
+    BINATTN_ERR_WORKSPACE = -5, /* workspace missing, misaligned or too small      */
+    BINATTN_ERR_DTYPE = -6,     /* unknown bias dtype                              */
+    BINATTN_ERR_LAUNCH = -7,    /* the HIP runtime refused a launch                */
+    BINATTN_ERR_VARIANT = -8,   /* unknown logits variant                          */
+    BINATTN_ERR_RANGE = -9      /* row range outside [0, N]                        */
+};
+
+enum { BINATTN_BIAS_BF16 = 1, BINATTN_BIAS_F32 = 2 };
+
+/* flags of binattn_forward */
+enum {
+    BINATTN_FLAG_NO_MU = 1,   /* ignore mu_q, mu_k (ablation row "no scale", Tab. 5) */
+    BINATTN_FLAG_NO_BIAS = 2  /* ignore bias (ablation rows without bias, Tab. 5)    */
+};
+
+/* variants of binattn_logits_debug */
+enum {
+    BINATTN_LOGITS_POPCOUNT = 0, /* d - 2*popcount(q XOR k) on the vector ALU (Sec. 4.1) */
+    BINATTN_LOGITS_MFMA_I8 = 1   /* +-1 int8 contraction on the matrix cores              */
+};
+
+int binattn_version(void);
+const char *binattn_strerror(int code);
+
+/*
+ * phi of Alg. 1 / Eq. 5 for Q and K in one launch sequence.
+ *   q, k      : bf16 [B, H, N, d] with element strides q_strides / k_strides.
+ *   q_bits,
+ *   k_bits    : out, uint32 [B, H, N, W] contiguous, W = ceil(d / 32).  Bit
+ *               (c & 31) of word (c >> 5) is 1 iff x[c] >= 0 under IEEE
+ *               comparison (+0 and -0 give 1, NaN gives 0); unused bits are 0.
+ *   mu_q, mu_k: out, float32 [B, H]: mean of |x| over the N*d elements of the
+ *               head (Eq. 5 text).  Accumulated with float atomics, so the last
+ *               bits may differ between runs.
+ */
+int binattn_pack_qk(const void *q, const void *k, int B, int H, int N, int d,
+                    const int64_t q_strides[3], const int64_t k_strides[3],
+                    uint32_t *q_bits, uint32_t *k_bits, float *mu_q, float *mu_k,
+                    void *stream);
+
+/* Bytes of scratch binattn_prepare_kv / binattn_attend / binattn_forward (and the
+ * debug entry points) need for this shape
+ * (0 if the shape is unsupported).  The workspace must be 256-byte aligned; its
+ * contents are private to the library and overwritten by every call. */
+size_t binattn_workspace_bytes(int B, int H, int N, int d);
+
+/*
+ * psi of Alg. 1 (Eq. 7) plus the operand set-up of the key side: quantises V
+ * to signed 8-bit codes with per-channel delta_v and lays the +-1 keys and the
+ * codes out in `workspace` the way the attention kernel reads them.
+ *   k_bits : as written by binattn_pack_qk.
+ *   v      : bf16 [B, H, N, d], strides v_strides.  Must be finite.
+ */
+int binattn_prepare_kv(const uint32_t *k_bits, const void *v, const int64_t v_strides[3], int B,
+                       int H, int N, int d, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The fused loop of Alg. 1 (logits of Eq. 6, online softmax, 8-bit P, integer
+ * P~.V~, final rescale) over a workspace filled by binattn_prepare_kv for the
+ * SAME (B, H, N, d).
+ *   q_bits     : as written by binattn_pack_qk.
+ *   mu_q, mu_k : float32 [B, H]; either may be NULL (taken as 1).
+ *   bias       : [.., N, N] of bias_dtype, element strides bias_strides for
+ *                (batch, head, row); a batch stride of 0 shares one bias over
+ *                the batch.  May be NULL (no bias).  Rows need no particular
+ *                alignment, but the fast load path needs a 16-byte aligned base
+ *                and strides that keep every row 16-byte aligned.
+ *   scale      : multiplies the +-1 inner product (1/sqrt(d) in Eq. 6); the
+ *                effective multiplier is scale * mu_q[b,h] * mu_k[b,h].
+ *   out        : bf16 [B, H, N, d], strides out_strides, rounded to nearest even
+ *                from fp32.
+ *   flags      : BINATTN_FLAG_*.
+ */
+int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k, const void *bias,
+                   int bias_dtype, const int64_t bias_strides[3], float scale, int B, int H, int N,
+                   int d, void *out, const int64_t out_strides[3], const void *workspace,
+                   size_t workspace_bytes, unsigned flags, void *stream);
+
+/*
+ * binattn_prepare_kv followed by binattn_attend (all of Alg. 1 after phi);
+ * arguments as above.
+ */
+int binattn_forward(const uint32_t *q_bits, const uint32_t *k_bits, const float *mu_q,
+                    const float *mu_k, const void *v, const int64_t v_strides[3],
+                    const void *bias, int bias_dtype, const int64_t bias_strides[3],
+                    float scale, int B, int H, int N, int d, void *out,
+                    const int64_t out_strides[3], void *workspace, size_t workspace_bytes,
+                    unsigned flags, void *stream);
+
+/*
+ * Integer logits I_ij = s_i . t_j of Sec. 4.1 for query rows
+ * [row_begin, row_end) of every head: int32 [B, H, row_end - row_begin, N]
+ * contiguous.  BINATTN_LOGITS_MFMA_I8 runs the same tile routine as the fused
+ * kernel and needs the workspace of binattn_workspace_bytes; POPCOUNT ignores
+ * the workspace arguments.
+ */
+int binattn_logits_debug(const uint32_t *q_bits, const uint32_t *k_bits, int B, int H, int N,
+                         int d, int row_begin, int row_end, int32_t *logits, int variant,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * psi alone (Eq. 7), exported in canonical layout for checking:
+ *   vq    : out, int8 [B, H, N, d] contiguous, code = rne(v / delta) in [-127, 127]
+ *   delta : out, float32 [B, H, d], delta = absmax over tokens / 127 (1 if the
+ *           channel is all zero); both divisions are IEEE fp32.
+ * Runs the same quantisation kernels as binattn_forward into `workspace` and
+ * then copies the codes out of the library's internal layout.
+ */
+int binattn_quant_v_debug(const void *v, const int64_t v_strides[3], int B, int H, int N, int d,
+                          int8_t *vq, float *delta, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BINATTN_H */

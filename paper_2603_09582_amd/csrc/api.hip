@@ -1,0 +1,230 @@
+// C ABI of libbinattn: argument validation (before anything is launched) and
+// the launch sequences.  See include/binattn.h for the contract.
+#include "binattn_internal.h"
+
+using namespace binattn;
+
+namespace {
+
+bool shape_ok(int B, int H, int N, int d) {
+    if (B < 1 || H < 1 || N < 1 || N > (1 << 24)) return false;
+    if (d < 8 || d > 128 || (d % 8) != 0) return false;
+    if ((int64_t)B * H >= ((int64_t)1 << 31) / 128) return false;
+    return true;
+}
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// Strides of a bf16 [B,H,N,d] tensor: non-negative, rows at least d apart and
+// every stride a multiple of 8 elements (16 bytes).
+int check_strides_bhnd(const int64_t st[3], const Shape &s, Strides3 *out) {
+    if (!st) return BINATTN_ERR_NULL;
+    for (int i = 0; i < 3; ++i)
+        if (st[i] < 0 || (st[i] % 8) != 0) return BINATTN_ERR_STRIDE;
+    if (s.N > 1 && st[2] < s.d) return BINATTN_ERR_STRIDE;
+    out->b = st[0]; out->h = st[1]; out->n = st[2];
+    return BINATTN_OK;
+}
+
+int check_workspace(const void *ws, size_t bytes, const Workspace &w) {
+    if (!ws) return BINATTN_ERR_WORKSPACE;
+    if (!aligned(ws, 256)) return BINATTN_ERR_WORKSPACE;
+    if (bytes < w.total) return BINATTN_ERR_WORKSPACE;
+    return BINATTN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int binattn_version(void) { return 100; }
+
+const char *binattn_strerror(int code) {
+    switch (code) {
+        case BINATTN_OK: return "ok";
+        case BINATTN_ERR_NULL: return "a required pointer is NULL";
+        case BINATTN_ERR_SHAPE: return "unsupported shape (need B,H,N >= 1, d a multiple of 8 in [8,128])";
+        case BINATTN_ERR_STRIDE: return "bad stride (negative, smaller than the row, or not a multiple of 8 elements)";
+        case BINATTN_ERR_ALIGN: return "base pointer not aligned as required";
+        case BINATTN_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or too small";
+        case BINATTN_ERR_DTYPE: return "unknown bias dtype";
+        case BINATTN_ERR_LAUNCH: return "HIP runtime refused the launch";
+        case BINATTN_ERR_VARIANT: return "unknown logits variant";
+        case BINATTN_ERR_RANGE: return "row range outside [0, N]";
+        default: return "unknown error code";
+    }
+}
+
+size_t binattn_workspace_bytes(int B, int H, int N, int d) {
+    if (!shape_ok(B, H, N, d)) return 0;
+    return make_workspace(make_shape(B, H, N, d)).total;
+}
+
+int binattn_pack_qk(const void *q, const void *k, int B, int H, int N, int d,
+                    const int64_t q_strides[3], const int64_t k_strides[3], uint32_t *q_bits,
+                    uint32_t *k_bits, float *mu_q, float *mu_k, void *stream) {
+    if (!q || !k || !q_bits || !k_bits || !mu_q || !mu_k) return BINATTN_ERR_NULL;
+    if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
+    const Shape s = make_shape(B, H, N, d);
+    Strides3 qs, ks;
+    int rc;
+    if ((rc = check_strides_bhnd(q_strides, s, &qs)) != BINATTN_OK) return rc;
+    if ((rc = check_strides_bhnd(k_strides, s, &ks)) != BINATTN_OK) return rc;
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(q_bits, 4) || !aligned(k_bits, 4) ||
+        !aligned(mu_q, 4) || !aligned(mu_k, 4))
+        return BINATTN_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if ((rc = launch_zero_f32(mu_q, mu_k, s.BH, st)) != BINATTN_OK) return rc;
+    if ((rc = launch_pack(q, qs, s, q_bits, mu_q, st)) != BINATTN_OK) return rc;
+    return launch_pack(k, ks, s, k_bits, mu_k, st);
+}
+
+int binattn_prepare_kv(const uint32_t *k_bits, const void *v, const int64_t v_strides[3], int B,
+                       int H, int N, int d, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!k_bits || !v) return BINATTN_ERR_NULL;
+    if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
+    const Shape s = make_shape(B, H, N, d);
+    const Workspace w = make_workspace(s);
+    Strides3 vs;
+    int rc;
+    if ((rc = check_strides_bhnd(v_strides, s, &vs)) != BINATTN_OK) return rc;
+    if (!aligned(v, 16) || !aligned(k_bits, 4)) return BINATTN_ERR_ALIGN;
+    if ((rc = check_workspace(workspace, workspace_bytes, w)) != BINATTN_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    if ((rc = launch_quant_v(v, vs, s, ws, w, st)) != BINATTN_OK) return rc;
+    return launch_expand_k(k_bits, s, reinterpret_cast<int8_t *>(ws + w.k8), st);
+}
+
+int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k, const void *bias,
+                   int bias_dtype, const int64_t bias_strides[3], float scale, int B, int H, int N,
+                   int d, void *out, const int64_t out_strides[3], const void *workspace,
+                   size_t workspace_bytes, unsigned flags, void *stream) {
+    if (!q_bits || !out) return BINATTN_ERR_NULL;
+    if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
+    const Shape s = make_shape(B, H, N, d);
+    const Workspace w = make_workspace(s);
+    Strides3 os;
+    int rc;
+    if ((rc = check_strides_bhnd(out_strides, s, &os)) != BINATTN_OK) return rc;
+    if (!aligned(out, 16) || !aligned(q_bits, 4)) return BINATTN_ERR_ALIGN;
+    if ((mu_q && !aligned(mu_q, 4)) || (mu_k && !aligned(mu_k, 4))) return BINATTN_ERR_ALIGN;
+
+    const bool use_bias = bias != nullptr && !(flags & BINATTN_FLAG_NO_BIAS);
+    int mode = BIAS_NONE;
+    Strides3 bs = {0, 0, 0};
+    if (use_bias) {
+        if (bias_dtype != BINATTN_BIAS_BF16 && bias_dtype != BINATTN_BIAS_F32) return BINATTN_ERR_DTYPE;
+        if (!bias_strides) return BINATTN_ERR_NULL;
+        for (int i = 0; i < 3; ++i)
+            if (bias_strides[i] < 0) return BINATTN_ERR_STRIDE;
+        if (N > 1 && bias_strides[2] < N) return BINATTN_ERR_STRIDE;
+        bs.b = bias_strides[0]; bs.h = bias_strides[1]; bs.n = bias_strides[2];
+        const int esz = bias_dtype == BINATTN_BIAS_BF16 ? 2 : 4;
+        if (!aligned(bias, esz)) return BINATTN_ERR_ALIGN;
+        const int per16 = 16 / esz;
+        const bool vec = aligned(bias, 16) && bs.b % per16 == 0 && bs.h % per16 == 0 && bs.n % per16 == 0;
+        if (bias_dtype == BINATTN_BIAS_BF16) mode = vec ? BIAS_BF16_VEC : BIAS_BF16_ANY;
+        else mode = vec ? BIAS_F32_VEC : BIAS_F32_ANY;
+    }
+    if ((rc = check_workspace(workspace, workspace_bytes, w)) != BINATTN_OK) return rc;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const char *ws = static_cast<const char *>(workspace);
+    FusedParams p;
+    p.q_bits = q_bits;
+    const bool use_mu = !(flags & BINATTN_FLAG_NO_MU);
+    p.mu_q = use_mu ? mu_q : nullptr;
+    p.mu_k = use_mu ? mu_k : nullptr;
+    p.bias = use_bias ? bias : nullptr;
+    p.bs = bs;
+    p.scale = scale;
+    p.out = static_cast<uint16_t *>(out);
+    p.os = os;
+    p.k8 = reinterpret_cast<const int8_t *>(ws + w.k8);
+    p.vt8 = reinterpret_cast<const int8_t *>(ws + w.vt8);
+    p.cs128 = reinterpret_cast<const int *>(ws + w.cs128);
+    p.delta = reinterpret_cast<const float *>(ws + w.delta);
+    p.B = B; p.H = H; p.N = N; p.d = d;
+    p.nblk = s.nblk; p.npad = s.npad;
+    p.nrb = (N + BR - 1) / BR;
+    p.total_wg = p.nrb * s.BH;
+    switch (s.DK) {
+        case 1: return launch_fused_dk<1>(p, mode, st);
+        case 2: return launch_fused_dk<2>(p, mode, st);
+        case 3: return launch_fused_dk<3>(p, mode, st);
+        case 4: return launch_fused_dk<4>(p, mode, st);
+        default: return BINATTN_ERR_SHAPE;
+    }
+}
+
+int binattn_forward(const uint32_t *q_bits, const uint32_t *k_bits, const float *mu_q,
+                    const float *mu_k, const void *v, const int64_t v_strides[3], const void *bias,
+                    int bias_dtype, const int64_t bias_strides[3], float scale, int B, int H, int N,
+                    int d, void *out, const int64_t out_strides[3], void *workspace,
+                    size_t workspace_bytes, unsigned flags, void *stream) {
+    // Validate the second stage's arguments before the first stage launches anything.
+    if (!q_bits || !k_bits || !v || !out) return BINATTN_ERR_NULL;
+    if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
+    const Shape s = make_shape(B, H, N, d);
+    Strides3 tmp;
+    int rc;
+    if ((rc = check_strides_bhnd(v_strides, s, &tmp)) != BINATTN_OK) return rc;
+    if ((rc = check_strides_bhnd(out_strides, s, &tmp)) != BINATTN_OK) return rc;
+    if (!aligned(v, 16) || !aligned(out, 16) || !aligned(q_bits, 4) || !aligned(k_bits, 4))
+        return BINATTN_ERR_ALIGN;
+    if ((mu_q && !aligned(mu_q, 4)) || (mu_k && !aligned(mu_k, 4))) return BINATTN_ERR_ALIGN;
+    if (bias != nullptr && !(flags & BINATTN_FLAG_NO_BIAS)) {
+        if (bias_dtype != BINATTN_BIAS_BF16 && bias_dtype != BINATTN_BIAS_F32) return BINATTN_ERR_DTYPE;
+        if (!bias_strides) return BINATTN_ERR_NULL;
+        for (int i = 0; i < 3; ++i)
+            if (bias_strides[i] < 0) return BINATTN_ERR_STRIDE;
+        if (N > 1 && bias_strides[2] < N) return BINATTN_ERR_STRIDE;
+        if (!aligned(bias, bias_dtype == BINATTN_BIAS_BF16 ? 2 : 4)) return BINATTN_ERR_ALIGN;
+    }
+    if ((rc = binattn_prepare_kv(k_bits, v, v_strides, B, H, N, d, workspace, workspace_bytes,
+                                 stream)) != BINATTN_OK)
+        return rc;
+    return binattn_attend(q_bits, mu_q, mu_k, bias, bias_dtype, bias_strides, scale, B, H, N, d, out,
+                          out_strides, workspace, workspace_bytes, flags, stream);
+}
+
+int binattn_logits_debug(const uint32_t *q_bits, const uint32_t *k_bits, int B, int H, int N, int d,
+                         int row_begin, int row_end, int32_t *logits, int variant, void *workspace,
+                         size_t workspace_bytes, void *stream) {
+    if (!q_bits || !k_bits || !logits) return BINATTN_ERR_NULL;
+    if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
+    if (row_begin < 0 || row_end < row_begin || row_end > N) return BINATTN_ERR_RANGE;
+    if (variant != BINATTN_LOGITS_POPCOUNT && variant != BINATTN_LOGITS_MFMA_I8) return BINATTN_ERR_VARIANT;
+    if (!aligned(q_bits, 4) || !aligned(k_bits, 4) || !aligned(logits, 4)) return BINATTN_ERR_ALIGN;
+    const Shape s = make_shape(B, H, N, d);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (variant == BINATTN_LOGITS_POPCOUNT)
+        return launch_logits_popcount(q_bits, k_bits, s, row_begin, row_end, logits, st);
+    const Workspace w = make_workspace(s);
+    int rc;
+    if ((rc = check_workspace(workspace, workspace_bytes, w)) != BINATTN_OK) return rc;
+    int8_t *k8 = reinterpret_cast<int8_t *>(static_cast<char *>(workspace) + w.k8);
+    if ((rc = launch_expand_k(k_bits, s, k8, st)) != BINATTN_OK) return rc;
+    return launch_logits_mfma(q_bits, k8, s, row_begin, row_end, logits, st);
+}
+
+int binattn_quant_v_debug(const void *v, const int64_t v_strides[3], int B, int H, int N, int d,
+                          int8_t *vq, float *delta, void *workspace, size_t workspace_bytes,
+                          void *stream) {
+    if (!v || !vq || !delta) return BINATTN_ERR_NULL;
+    if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
+    const Shape s = make_shape(B, H, N, d);
+    const Workspace w = make_workspace(s);
+    Strides3 vs;
+    int rc;
+    if ((rc = check_strides_bhnd(v_strides, s, &vs)) != BINATTN_OK) return rc;
+    if (!aligned(v, 16) || !aligned(delta, 4)) return BINATTN_ERR_ALIGN;
+    if ((rc = check_workspace(workspace, workspace_bytes, w)) != BINATTN_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    if ((rc = launch_quant_v(v, vs, s, ws, w, st)) != BINATTN_OK) return rc;
+    return launch_export_vq(s, ws, w, vq, delta, st);
+}
+
+}  // extern "C"

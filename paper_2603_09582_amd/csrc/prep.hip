@@ -1,0 +1,213 @@
+// Operand preparation for the fused kernel:
+//   * K sign words -> +-1 int8 rows in the order the QK MFMA tile wants them
+//   * psi of Alg. 1 (Eq. 7): per-channel absmax of V, delta_v, signed 8-bit
+//     codes stored channel-major, and 128 * column sums per key block (the
+//     correction term of the signed P operand, see fused.hip)
+// All three are HBM-bound streaming kernels.
+#include "binattn_internal.h"
+
+namespace binattn {
+
+constexpr int PREP_THREADS = 256;
+
+// 4 sign bits -> 4 bytes holding +1 (bit set) or -1 (bit clear).
+__device__ __forceinline__ unsigned expand_nibble_pm1(unsigned nib) {
+    unsigned x = (nib * 0x00204081u) & 0x01010101u;  // bit i -> byte i
+    return x | ((x ^ 0x01010101u) * 0xFFu);          // 0x01 where set, 0xFF where clear
+}
+
+// Row position inside a key block <-> key offset.  The fused kernel's lane
+// (g = lane / 32) holds, for MFMA tile t and accumulator register r, the key
+// j0 + 64 g + 16 t + r; the MFMA puts accumulator register r of lane group g
+// at tile row m = 8 (r / 4) + 4 g + (r % 4).  Rows are stored at position
+// 32 t + m so that the A operand reads consecutive LDS rows.
+__device__ __forceinline__ int key_of_position(int pos) {
+    const int t = pos >> 5, m = pos & 31;
+    const int g = (m >> 2) & 1;
+    const int r = ((m >> 3) << 2) | (m & 3);
+    return 64 * g + 16 * t + r;
+}
+
+__global__ __launch_bounds__(PREP_THREADS) void expand_k_kernel(const uint32_t *__restrict__ k_bits,
+                                                                int N, int d, int W, int nblk,
+                                                                int8_t *__restrict__ k8) {
+    const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
+    const int DKP = 32 * W;
+    const uint32_t *kb = k_bits + (int64_t)bh * N * W;
+    int8_t *dst = k8 + ((int64_t)bh * nblk + blk) * BV * DKP;
+    for (int i = threadIdx.x; i < BV * W; i += PREP_THREADS) {
+        const int pos = i / W, w = i % W;
+        const int key = blk * BV + key_of_position(pos);
+        const uint32_t word = key < N ? kb[(int64_t)key * W + w] : 0u;
+        const int valid = key < N ? d - 32 * w : 0;  // real channels in this word
+        uint32_t o[8];
+#pragma unroll
+        for (int n = 0; n < 8; ++n)
+            o[n] = (4 * n < valid) ? expand_nibble_pm1((word >> (4 * n)) & 0xFu) : 0u;
+        uint4 *p = reinterpret_cast<uint4 *>(dst + (int64_t)pos * DKP + 32 * w);
+        p[0] = make_uint4(o[0], o[1], o[2], o[3]);
+        p[1] = make_uint4(o[4], o[5], o[6], o[7]);
+    }
+}
+
+__device__ __forceinline__ void unpack8(uint4 w, float f[8]) {
+    const unsigned dw[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = __uint_as_float(dw[i] << 16);
+        f[2 * i + 1] = __uint_as_float(dw[i] & 0xffff0000u);
+    }
+}
+
+// Partial absmax over VCHUNK token rows: amax[bh][chunk][c].
+template <int C16>
+__global__ __launch_bounds__(PREP_THREADS) void v_absmax_kernel(const uint16_t *__restrict__ v,
+                                                                Strides3 vs, int H, int N, int DKP,
+                                                                int nchunk,
+                                                                float *__restrict__ amax) {
+    constexpr int RT = PREP_THREADS / C16;  // token rows per pass
+    constexpr int D = 8 * C16;
+    __shared__ float smax[RT * D];
+    const int chunk = blockIdx.x % nchunk, bh = blockIdx.x / nchunk;
+    const int b = bh / H, h = bh % H;
+    const uint16_t *vb = v + (int64_t)b * vs.b + (int64_t)h * vs.h;
+    const int n0 = chunk * VCHUNK, n1 = min(N, n0 + VCHUNK);
+    const int c = threadIdx.x % C16, r0 = threadIdx.x / C16;
+    if (r0 < RT) {
+        float m[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) m[i] = 0.0f;
+        for (int n = n0 + r0; n < n1; n += RT) {
+            float f[8];
+            unpack8(*reinterpret_cast<const uint4 *>(vb + (int64_t)n * vs.n + 8 * c), f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) m[i] = fmaxf(m[i], fabsf(f[i]));
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) smax[r0 * D + 8 * c + i] = m[i];
+    }
+    __syncthreads();
+    if (threadIdx.x < D) {
+        float a = 0.0f;
+        for (int r = 0; r < RT; ++r) a = fmaxf(a, smax[r * D + threadIdx.x]);
+        amax[((int64_t)bh * nchunk + chunk) * DKP + threadIdx.x] = a;
+    }
+}
+
+// One key block of one head: delta_v, codes (channel-major) and 128 * column sums.
+template <int C16>
+__global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(const uint16_t *__restrict__ v,
+                                                               Strides3 vs, int H, int N, int DKP,
+                                                               int nchunk, int nblk,
+                                                               const float *__restrict__ amax,
+                                                               float *__restrict__ delta,
+                                                               int8_t *__restrict__ vt8,
+                                                               int *__restrict__ cs128) {
+    constexpr int D = 8 * C16;
+    constexpr int LDT = BV + 16;  // LDS row pitch in bytes
+    __shared__ float sdelta[D];
+    __shared__ __attribute__((aligned(16))) int8_t tile[128 * LDT];  // up to DKP = 128 rows
+    const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
+    const int npad = nblk * BV;
+    const int b = bh / H, h = bh % H;
+    const uint16_t *vb = v + (int64_t)b * vs.b + (int64_t)h * vs.h;
+
+    if (threadIdx.x < D) {
+        float a = 0.0f;
+        for (int i = 0; i < nchunk; ++i)
+            a = fmaxf(a, amax[((int64_t)bh * nchunk + i) * DKP + threadIdx.x]);
+        // Eq. 7 scale: absmax / 127 (IEEE fp32 division); 1 for an all-zero channel.
+        const float dl = (a == 0.0f) ? 1.0f : __fdiv_rn(a, 127.0f);
+        sdelta[threadIdx.x] = dl;
+        if (blk == 0) delta[(int64_t)bh * DKP + threadIdx.x] = dl;
+    }
+    for (int i = threadIdx.x; i < DKP * LDT / 4; i += PREP_THREADS)
+        reinterpret_cast<uint32_t *>(tile)[i] = 0u;
+    __syncthreads();
+
+    const int j0 = blk * BV;
+    const int nrow = min(BV, N - j0);
+    for (int e = threadIdx.x; e < nrow * C16; e += PREP_THREADS) {
+        const int jl = e / C16, c = e % C16;
+        float f[8];
+        unpack8(*reinterpret_cast<const uint4 *>(vb + (int64_t)(j0 + jl) * vs.n + 8 * c), f);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            // Eq. 7: code = round-to-nearest-even(v / delta), clamped to [-127, 127]
+            float q = rintf(__fdiv_rn(f[i], sdelta[8 * c + i]));
+            q = fminf(fmaxf(q, -127.0f), 127.0f);
+            tile[(8 * c + i) * LDT + jl] = (int8_t)(int)q;
+        }
+    }
+    __syncthreads();
+
+    int8_t *vt = vt8 + (int64_t)bh * DKP * npad;
+    for (int i = threadIdx.x; i < DKP * (BV / 16); i += PREP_THREADS) {
+        const int c = i / (BV / 16), part = i % (BV / 16);
+        const uint4 val = *reinterpret_cast<const uint4 *>(tile + c * LDT + 16 * part);
+        *reinterpret_cast<uint4 *>(vt + (int64_t)c * npad + j0 + 16 * part) = val;
+    }
+    if (threadIdx.x < DKP) {
+        int sum = 0;
+        for (int j = 0; j < BV; ++j) sum += (int)tile[threadIdx.x * LDT + j];
+        cs128[((int64_t)bh * nblk + blk) * DKP + threadIdx.x] = 128 * sum;
+    }
+}
+
+// Codes and delta from the private layout into [B,H,N,d] / [B,H,d].
+__global__ void export_vq_kernel(const int8_t *__restrict__ vt8, const float *__restrict__ dl,
+                                 int N, int d, int DKP, int npad, int nper,
+                                 int8_t *__restrict__ vq, float *__restrict__ delta) {
+    const int bh = blockIdx.x / nper;
+    const int64_t i = (int64_t)(blockIdx.x % nper) * blockDim.x + threadIdx.x;
+    if (i < (int64_t)N * d) {
+        const int n = (int)(i / d), c = (int)(i % d);
+        vq[(int64_t)bh * N * d + i] = vt8[((int64_t)bh * DKP + c) * npad + n];
+    }
+    if (i < d) delta[(int64_t)bh * d + i] = dl[(int64_t)bh * DKP + i];
+}
+
+int launch_expand_k(const uint32_t *k_bits, const Shape &s, int8_t *k8, hipStream_t stream) {
+    hipLaunchKernelGGL(expand_k_kernel, dim3((unsigned)s.nblk * s.BH), dim3(PREP_THREADS), 0,
+                       stream, k_bits, s.N, s.d, s.W, s.nblk, k8);
+    return check_launch();
+}
+
+template <int C16>
+static void launch_quant_v_t(const void *v, Strides3 vs, const Shape &s, char *ws,
+                             const Workspace &w, hipStream_t stream) {
+    const uint16_t *vp = static_cast<const uint16_t *>(v);
+    float *amax = reinterpret_cast<float *>(ws + w.amax);
+    float *delta = reinterpret_cast<float *>(ws + w.delta);
+    int8_t *vt8 = reinterpret_cast<int8_t *>(ws + w.vt8);
+    int *cs = reinterpret_cast<int *>(ws + w.cs128);
+    hipLaunchKernelGGL(v_absmax_kernel<C16>, dim3((unsigned)s.nchunk * s.BH), dim3(PREP_THREADS),
+                       0, stream, vp, vs, s.H, s.N, s.DKP, s.nchunk, amax);
+    hipLaunchKernelGGL(v_quant_kernel<C16>, dim3((unsigned)s.nblk * s.BH), dim3(PREP_THREADS), 0,
+                       stream, vp, vs, s.H, s.N, s.DKP, s.nchunk, s.nblk, amax, delta, vt8, cs);
+}
+
+int launch_quant_v(const void *v, Strides3 vs, const Shape &s, char *ws, const Workspace &w,
+                   hipStream_t stream) {
+    switch (s.d / 8) {
+#define CASE(c) case c: launch_quant_v_t<c>(v, vs, s, ws, w, stream); break;
+        CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8)
+        CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14) CASE(15) CASE(16)
+#undef CASE
+        default: return BINATTN_ERR_SHAPE;
+    }
+    return check_launch();
+}
+
+int launch_export_vq(const Shape &s, const char *ws, const Workspace &w, int8_t *vq, float *delta,
+                     hipStream_t stream) {
+    const int64_t total = (int64_t)s.N * s.d;
+    const int nper = (int)((total + 255) / 256);
+    hipLaunchKernelGGL(export_vq_kernel, dim3((unsigned)nper * s.BH), dim3(256), 0, stream,
+                       reinterpret_cast<const int8_t *>(ws + w.vt8),
+                       reinterpret_cast<const float *>(ws + w.delta), s.N, s.d, s.DKP, s.npad,
+                       nper, vq, delta);
+    return check_launch();
+}
+
+}  // namespace binattn
