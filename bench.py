@@ -46,17 +46,18 @@ def parse():
     ap.add_argument("--workload", default="vit_hires")
     ap.add_argument("--others", action="store_true", help="also time the other workloads (extra field)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-bias", action="store_true", help="run without the bias term (not the headline config)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
 
-def run_workload(name, steps, warmup):
+def run_workload(name, steps, warmup, with_bias=True):
     import torch
     from paper_2603_09582_amd import binding as ba
     from paper_2603_09582_amd import workloads as wl
 
     w = wl.WORKLOADS[name]
-    x = wl.make_inputs(w, device="cuda")
+    x = wl.make_inputs(w, device="cuda", with_bias=with_bias)
     B, H, N, d = w.B, w.H, w.N, w.d
     W = (d + 31) // 32
     dev = x.q.device
@@ -155,7 +156,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     from paper_2603_09582_amd import workloads as wl
 
-    res, x = run_workload(a.workload, a.steps, a.warmup)
+    res, x = run_workload(a.workload, a.steps, a.warmup, with_bias=not a.no_bias)
     line = {
         "metric": "attention TOPS-equiv (4*B*H*N^2*d/s), whole hot path (pack_qk + prepare_kv + attend)",
         "value": res["tops_equiv"], "unit": "TOPS-equiv", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -190,7 +191,9 @@ def main():
             del x
             torch.cuda.empty_cache()
             _, x = run_workload(a.workload, 1, 0)
-    if not a.no_cpu_baseline:
+    if a.no_bias:
+        line["config"]["workload"] += " -- WITHOUT bias (diagnostic run)"
+    if not a.no_cpu_baseline and not a.no_bias:
         line["cpu_baseline"] = cpu_baseline(x, a.cpu_seconds)
     print(json.dumps(line))
 

@@ -60,8 +60,10 @@ enum {
 
 /* variants of binattn_logits_debug */
 enum {
-    BINATTN_LOGITS_POPCOUNT = 0, /* d - 2*popcount(q XOR k) on the vector ALU (Sec. 4.1) */
-    BINATTN_LOGITS_MFMA_I8 = 1   /* +-1 int8 contraction on the matrix cores              */
+    BINATTN_LOGITS_POPCOUNT = 0, /* d - 2*popcount(q XOR k) on the vector ALU (Sec. 4.1)   */
+    BINATTN_LOGITS_MFMA_I8 = 1,  /* +-1 int8 contraction on the matrix cores                */
+    BINATTN_LOGITS_MFMA_FP4 = 2  /* +-1.0 FP4 contraction, fp32 accumulate (exact); the form
+                                    the fused kernel uses                                   */
 };
 
 int binattn_version(void);
@@ -135,9 +137,9 @@ int binattn_forward(const uint32_t *q_bits, const uint32_t *k_bits, const float 
 /*
  * Integer logits I_ij = s_i . t_j of Sec. 4.1 for query rows
  * [row_begin, row_end) of every head: int32 [B, H, row_end - row_begin, N]
- * contiguous.  BINATTN_LOGITS_MFMA_I8 runs the same tile routine as the fused
- * kernel and needs the workspace of binattn_workspace_bytes; POPCOUNT ignores
- * the workspace arguments.
+ * contiguous.  BINATTN_LOGITS_MFMA_FP4 runs the same tile routine as the fused
+ * kernel and needs the workspace of binattn_workspace_bytes (it overwrites the
+ * key part); the other variants ignore the workspace arguments.
  */
 int binattn_logits_debug(const uint32_t *q_bits, const uint32_t *k_bits, int B, int H, int N,
                          int d, int row_begin, int row_end, int32_t *logits, int variant,

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libbinattn.so")
 
 BIAS_BF16, BIAS_F32 = 1, 2
 FLAG_NO_MU, FLAG_NO_BIAS = 1, 2
-LOGITS_POPCOUNT, LOGITS_MFMA_I8 = 0, 1
+LOGITS_POPCOUNT, LOGITS_MFMA_I8, LOGITS_MFMA_FP4 = 0, 1, 2
 
 EXPORTS = ["binattn_version", "binattn_strerror", "binattn_pack_qk", "binattn_workspace_bytes",
            "binattn_prepare_kv", "binattn_attend", "binattn_forward", "binattn_logits_debug",
@@ -182,7 +182,7 @@ def logits_debug(q_bits: torch.Tensor, k_bits: torch.Tensor, d: int, row_begin: 
                  variant: int, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     B, H, N, _ = q_bits.shape
     out = torch.empty(B, H, row_end - row_begin, N, dtype=torch.int32, device=q_bits.device)
-    if workspace is None and variant != LOGITS_POPCOUNT:
+    if workspace is None and variant == LOGITS_MFMA_FP4:
         workspace = alloc_workspace(B, H, N, d, q_bits.device)
     rc = lib().binattn_logits_debug(
         q_bits.data_ptr(), k_bits.data_ptr(), B, H, N, d, row_begin, row_end, out.data_ptr(),

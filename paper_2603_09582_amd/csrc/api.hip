@@ -93,7 +93,7 @@ int binattn_prepare_kv(const uint32_t *k_bits, const void *v, const int64_t v_st
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
     if ((rc = launch_quant_v(v, vs, s, ws, w, st)) != BINATTN_OK) return rc;
-    return launch_expand_k(k_bits, s, reinterpret_cast<int8_t *>(ws + w.k8), st);
+    return launch_expand_k(k_bits, s, ws, w, st);
 }
 
 int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k, const void *bias,
@@ -124,8 +124,14 @@ int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
         if (!aligned(bias, esz)) return BINATTN_ERR_ALIGN;
         const int per16 = 16 / esz;
         const bool vec = aligned(bias, 16) && bs.b % per16 == 0 && bs.h % per16 == 0 && bs.n % per16 == 0;
-        if (bias_dtype == BINATTN_BIAS_BF16) mode = vec ? BIAS_BF16_VEC : BIAS_BF16_ANY;
-        else mode = vec ? BIAS_F32_VEC : BIAS_F32_ANY;
+        if (bias_dtype == BINATTN_BIAS_BF16) {
+            mode = vec ? BIAS_BF16_VEC : BIAS_BF16_ANY;
+            // LDS staging needs whole 16-byte chunks inside the row and LDS room for two
+            // workgroups per CU (d <= 96)
+            if (vec && N % 8 == 0 && s.DK <= 3) mode = BIAS_BF16_LDS;
+        } else {
+            mode = vec ? BIAS_F32_VEC : BIAS_F32_ANY;
+        }
     }
     if ((rc = check_workspace(workspace, workspace_bytes, w)) != BINATTN_OK) return rc;
 
@@ -141,12 +147,10 @@ int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
     p.scale = scale;
     p.out = static_cast<uint16_t *>(out);
     p.os = os;
-    p.k8 = reinterpret_cast<const int8_t *>(ws + w.k8);
-    p.vt8 = reinterpret_cast<const int8_t *>(ws + w.vt8);
-    p.cs128 = reinterpret_cast<const int *>(ws + w.cs128);
+    p.img = ws + w.img;
     p.delta = reinterpret_cast<const float *>(ws + w.delta);
     p.B = B; p.H = H; p.N = N; p.d = d;
-    p.nblk = s.nblk; p.npad = s.npad;
+    p.nblk = s.nblk;
     p.nrb = (N + BR - 1) / BR;
     p.total_wg = p.nrb * s.BH;
     switch (s.DK) {
@@ -195,18 +199,22 @@ int binattn_logits_debug(const uint32_t *q_bits, const uint32_t *k_bits, int B, 
     if (!q_bits || !k_bits || !logits) return BINATTN_ERR_NULL;
     if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
     if (row_begin < 0 || row_end < row_begin || row_end > N) return BINATTN_ERR_RANGE;
-    if (variant != BINATTN_LOGITS_POPCOUNT && variant != BINATTN_LOGITS_MFMA_I8) return BINATTN_ERR_VARIANT;
+    if (variant != BINATTN_LOGITS_POPCOUNT && variant != BINATTN_LOGITS_MFMA_I8 &&
+        variant != BINATTN_LOGITS_MFMA_FP4)
+        return BINATTN_ERR_VARIANT;
     if (!aligned(q_bits, 4) || !aligned(k_bits, 4) || !aligned(logits, 4)) return BINATTN_ERR_ALIGN;
     const Shape s = make_shape(B, H, N, d);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (variant == BINATTN_LOGITS_POPCOUNT)
         return launch_logits_popcount(q_bits, k_bits, s, row_begin, row_end, logits, st);
+    if (variant == BINATTN_LOGITS_MFMA_I8)
+        return launch_logits_i8(q_bits, k_bits, s, row_begin, row_end, logits, st);
     const Workspace w = make_workspace(s);
     int rc;
     if ((rc = check_workspace(workspace, workspace_bytes, w)) != BINATTN_OK) return rc;
-    int8_t *k8 = reinterpret_cast<int8_t *>(static_cast<char *>(workspace) + w.k8);
-    if ((rc = launch_expand_k(k_bits, s, k8, st)) != BINATTN_OK) return rc;
-    return launch_logits_mfma(q_bits, k8, s, row_begin, row_end, logits, st);
+    char *ws = static_cast<char *>(workspace);
+    if ((rc = launch_expand_k(k_bits, s, ws, w, st)) != BINATTN_OK) return rc;
+    return launch_logits_fp4(q_bits, ws, w, s, row_begin, row_end, logits, st);
 }
 
 int binattn_quant_v_debug(const void *v, const int64_t v_strides[3], int B, int H, int N, int d,

@@ -1,16 +1,22 @@
 // Device routines shared by the fused attention kernel and the logits export:
-// the LDS tile layout of one key/value block and the +-1 int8 QK MFMA tile.
+// the per-block operand image, its asynchronous copy into LDS, and the QK tile
+// on the matrix cores.
 //
-// Register/lane convention (wave64, v_mfma_i32_32x32x32_i8, D = A*B + C):
-//   A is 32 x 32 (rows x k), B is 32 x 32 (k x cols); lane L feeds row/col
-//   (L & 31) with the 16 k-slots of group g = L >> 5.  A and B use the same
-//   slot numbering, so any consistent assignment of channels (or keys) to
-//   slots gives the same contraction.
+// Register/lane convention (wave64, 32x32 MFMA tiles, D = A*B + C):
+//   lane L feeds row (A) / column (B) number (L & 31) with the k-slots of group
+//   g = L >> 5.  A and B use the same slot numbering, so any consistent
+//   assignment of channels (or keys) to slots gives the same contraction.
 //   D: lane L holds column (L & 31); register r holds row 8(r/4) + 4g + (r%4).
 // The kernels put KEYS (resp. value channels) on the A side and QUERIES on the
 // B side, so that every lane owns one query row: all softmax statistics are
 // lane-local, and the P tile a lane produces is already in B-operand order for
 // the P.V contraction (no LDS round trip).
+//
+// QK runs as v_mfma_f32_32x32x64_f8f6f4 with FP4 (e2m1) operands: +1.0 and -1.0
+// are exact in FP4, the products and the fp32 accumulation of at most 128 of
+// them are exact, so the result is the integer logit of Sec. 4.1 already in
+// fp32 (no int->float conversion), and the accumulator input carries the bias
+// term of Eq. 6 for free.  An int8 form of the same tile is kept for comparison.
 #pragma once
 
 #include "binattn_internal.h"
@@ -18,75 +24,77 @@
 namespace binattn {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
-typedef unsigned u4v __attribute__((ext_vector_type(4)));  // 16-byte staging register
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned u4v __attribute__((ext_vector_type(4)));  // 16-byte register
 
 constexpr int FUSED_THREADS = 256;
 constexpr int KT = BV / 32;  // MFMA key tiles per block
 
-template <int DK>
-struct Tiles {
-    static constexpr int DKP = 32 * DK;
-    static constexpr int KP = DKP + 16;  // K row pitch (bytes); +16 keeps b128 reads conflict-free
-    static constexpr int VP = BV + 16;   // V^T row pitch (bytes)
-    int8_t k8[BV * KP];    // [position in block][channel]  +-1 / 0
-    int8_t vt[DKP * VP];   // [channel][key offset]         V codes
-    int cs[DKP];           // 128 * sum over the block's keys of the V codes
-};
+// FP4 e2m1 codes
+constexpr unsigned FP4_PLUS1 = 0x2u, FP4_MINUS1 = 0xAu;
 
-// 4 sign bits -> 4 bytes holding +1 (bit set) or -1 (bit clear).
-__device__ __forceinline__ unsigned pm1_bytes(unsigned nib) {
-    unsigned x = (nib * 0x00204081u) & 0x01010101u;
-    return x | ((x ^ 0x01010101u) * 0xFFu);
+// 8 sign bits -> 8 FP4 nibbles (bit i -> nibble i): +1.0 where set, -1.0 where clear.
+__device__ __forceinline__ unsigned fp4_pm1_from_bits8(unsigned b) {
+    unsigned s = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s |= ((b >> i) & 1u) << (4 * i);
+    return 0xAAAAAAAAu - (s << 3);  // 0xA - 8 = 0x2 where the bit is set
 }
 
-// B operand of the QK tile for this lane's query row: +-1 bytes of channels
-// 32 s + 16 g + [0, 16), zero beyond d.
-template <int DK>
-__device__ __forceinline__ void load_q_operand(const uint32_t *__restrict__ q_words, int d, int g,
-                                               v4i qB[DK]) {
+// B operand of the QK tile for this lane's query row: FP4 codes of channels
+// 64 s + 32 g + [0, 32) in 16 bytes, zero beyond d.  `flip` negates the row,
+// `zero` clears it (used for a non-positive or vanishing logit multiplier).
+template <int DK2>
+__device__ __forceinline__ void load_q_operand(const uint32_t *__restrict__ q_words, int W, int d,
+                                               int g, bool flip, bool zero, v4i qB[DK2]) {
 #pragma unroll
-    for (int s = 0; s < DK; ++s) {
-        const unsigned half = (q_words[s] >> (16 * g)) & 0xffffu;
+    for (int s = 0; s < DK2; ++s) {
+        const int w = 2 * s + g;
+        unsigned word = w < W ? q_words[w] : 0u;
+        if (flip) word = ~word;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int c0 = 32 * s + 16 * g + 4 * i;
-            qB[s][i] = c0 < d ? (int)pm1_bytes((half >> (4 * i)) & 0xFu) : 0;
+            const int c0 = 32 * w + 8 * i;
+            qB[s][i] = (c0 < d && !zero) ? (int)fp4_pm1_from_bits8((word >> (8 * i)) & 0xFFu) : 0;
         }
     }
 }
 
-// Integer logits of MFMA tile t of the block in LDS: for this lane's query,
-// register r is the +-1 inner product with key (block start + 64 g + 16 t + r).
+// QK tile t of the block image at `img`: for this lane's query, register r is
+// cin[r] + (s_i . t_j) with key j = block start + 64 g + 16 t + r.
 template <int DK>
-__device__ __forceinline__ v16i qk_tile(const Tiles<DK> &T, int t, int m, int g, const v4i qB[DK]) {
-    v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+__device__ __forceinline__ v16f qk_tile(const char *img, int t, int m, int g,
+                                        const v4i qB[(DK + 1) / 2], v16f cin) {
+    using L = Image<DK>;
 #pragma unroll
-    for (int s = 0; s < DK; ++s) {
-        const v4i a = *reinterpret_cast<const v4i *>(T.k8 + (32 * t + m) * Tiles<DK>::KP + 32 * s +
-                                                     16 * g);
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qB[s], acc, 0, 0, 0);
+    for (int s = 0; s < L::DK2; ++s) {
+        const v4i a = *reinterpret_cast<const v4i *>(img + L::K_OFF + (32 * t + m) * L::KP + 32 * s + 16 * g);
+        const v8i a8 = {a[0], a[1], a[2], a[3], 0, 0, 0, 0};
+        const v8i b8 = {qB[s][0], qB[s][1], qB[s][2], qB[s][3], 0, 0, 0, 0};
+        cin = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, cin, 4, 4, 0, 0, 0, 0);
     }
-    return acc;
+    return cin;
 }
 
-// Cooperative copy of the K part of block `blk` (contiguous in the workspace).
+// Asynchronous copy of one block image (L::BYTES, a multiple of 1 KiB) from
+// global memory straight into LDS: each wave moves 1 KiB per instruction
+// (64 lanes x 16 bytes, LDS address = base + 16 * lane).
 template <int DK>
-__device__ __forceinline__ void load_k_regs(const int8_t *__restrict__ k8_head, int blk,
-                                            u4v kreg[DK]) {
-    const u4v *src = reinterpret_cast<const u4v *>(k8_head + (int64_t)blk * BV * (32 * DK));
+__device__ __forceinline__ void dma_image(const char *__restrict__ gsrc, char *ldst, int wave, int lane) {
+    using L = Image<DK>;
+    constexpr int NCH = L::BYTES / 1024;
 #pragma unroll
-    for (int i = 0; i < DK; ++i) kreg[i] = src[threadIdx.x + FUSED_THREADS * i];
-}
-
-template <int DK>
-__device__ __forceinline__ void store_k_regs(Tiles<DK> &T, const u4v kreg[DK]) {
-#pragma unroll
-    for (int i = 0; i < DK; ++i) {
-        const int ch = threadIdx.x + FUSED_THREADS * i;
-        const int row = ch / (2 * DK), part = ch % (2 * DK);
-        *reinterpret_cast<u4v *>(T.k8 + row * Tiles<DK>::KP + 16 * part) = kreg[i];
+    for (int i = 0; i < (NCH + 3) / 4; ++i) {
+        const int c = wave + 4 * i;
+        if (c < NCH)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(gsrc + c * 1024 + lane * 16),
+                (__attribute__((address_space(3))) void *)(ldst + c * 1024), 16, 0, 0);
     }
 }
+
+__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 }  // namespace binattn

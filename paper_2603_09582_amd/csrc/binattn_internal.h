@@ -41,24 +41,58 @@ inline Shape make_shape(int B, int H, int N, int d) {
     return s;
 }
 
+// Operand image of one key/value block (BV keys) of one head, stored in the
+// workspace exactly as the attention kernel wants it in LDS, so that a block is
+// one flat asynchronous copy:
+//   K  [BV positions][KP bytes]  FP4 codes of the +-1 keys (0 beyond d / beyond N),
+//                                32 bytes per 64 channels, rows in MFMA order
+//   VT [DKP channels][VP bytes]  V codes, channel-major, BV key bytes per row
+//   CS [DKP] int32               PV_MAGIC + 128 * (sum of the block's V codes)
+// The pitches KP and VP carry 16 bytes of padding: 16-byte reads of 8
+// consecutive rows then fall into 8 different bank groups.
+template <int DK>
+struct Image {
+    static constexpr int DK2 = (DK + 1) / 2;       // 64-channel groups of the QK contraction
+    static constexpr int DKP = 32 * DK;            // padded channel count of V
+    static constexpr int KP = 32 * DK2 + 16;
+    static constexpr int VP = BV + 16;
+    static constexpr int K_OFF = 0;
+    static constexpr int V_OFF = BV * KP;
+    static constexpr int CS_OFF = V_OFF + DKP * VP;
+    static constexpr int BYTES = (CS_OFF + DKP * 4 + 1023) / 1024 * 1024;
+};
+
+inline int image_bytes(int DK) {
+    switch (DK) {
+        case 1: return Image<1>::BYTES;
+        case 2: return Image<2>::BYTES;
+        case 3: return Image<3>::BYTES;
+        default: return Image<4>::BYTES;
+    }
+}
+
+// The int32 P.V accumulator of a block starts from PV_MAGIC + 128 * colsum: read
+// as fp32 bits the finished accumulator is then 1.5 * 2^23 + (block result),
+// exact while |block result| < 2^22 (128 keys * 255 * 127 = 4 145 280 fits).
+constexpr int PV_MAGIC_BITS = 0x4B400000;
+constexpr float PV_MAGIC_F = 12582912.0f;
+
 // Private workspace layout (all offsets 256-byte aligned).
-//   k8    int8  [BH][nblk][BV rows in MFMA order][DKP]   +-1 keys, 0 in padding
-//   vt8   int8  [BH][DKP][npad]                          V codes, channel-major
-//   cs128 int32 [BH][nblk][DKP]                          128 * column sums of a key block
+//   img   bytes [BH][nblk][Image<DK>::BYTES]
 //   delta f32   [BH][DKP]
-//   amax  f32   [BH][nchunk][DKP]                        partial absmax of V
+//   amax  f32   [BH][nchunk][DKP]           partial absmax of V
 struct Workspace {
-    size_t k8, vt8, cs128, delta, amax, total;
+    size_t img, delta, amax, total;
+    int img_bytes;
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
 inline Workspace make_workspace(const Shape &s) {
     Workspace w;
+    w.img_bytes = image_bytes(s.DK);
     size_t off = 0;
-    w.k8 = off;    off = align256(off + (size_t)s.BH * s.npad * s.DKP);
-    w.vt8 = off;   off = align256(off + (size_t)s.BH * s.DKP * s.npad);
-    w.cs128 = off; off = align256(off + (size_t)s.BH * s.nblk * s.DKP * 4);
+    w.img = off;   off = align256(off + (size_t)s.BH * s.nblk * w.img_bytes);
     w.delta = off; off = align256(off + (size_t)s.BH * s.DKP * 4);
     w.amax = off;  off = align256(off + (size_t)s.BH * s.nchunk * s.DKP * 4);
     w.total = off;
@@ -73,22 +107,26 @@ struct Strides3 {
 int launch_pack(const void *x, Strides3 xs, const Shape &s, uint32_t *bits, float *mu,
                 hipStream_t stream);
 int launch_zero_f32(float *a, float *b, int n, hipStream_t stream);
-int launch_expand_k(const uint32_t *k_bits, const Shape &s, int8_t *k8, hipStream_t stream);
+int launch_expand_k(const uint32_t *k_bits, const Shape &s, char *ws, const Workspace &w,
+                    hipStream_t stream);
 int launch_quant_v(const void *v, Strides3 vs, const Shape &s, char *ws, const Workspace &w,
                    hipStream_t stream);
 int launch_export_vq(const Shape &s, const char *ws, const Workspace &w, int8_t *vq, float *delta,
                      hipStream_t stream);
 int launch_logits_popcount(const uint32_t *q_bits, const uint32_t *k_bits, const Shape &s,
                            int row_begin, int row_end, int32_t *logits, hipStream_t stream);
-int launch_logits_mfma(const uint32_t *q_bits, const int8_t *k8, const Shape &s, int row_begin,
-                       int row_end, int32_t *logits, hipStream_t stream);
+int launch_logits_fp4(const uint32_t *q_bits, const char *ws, const Workspace &w, const Shape &s,
+                      int row_begin, int row_end, int32_t *logits, hipStream_t stream);
+int launch_logits_i8(const uint32_t *q_bits, const uint32_t *k_bits, const Shape &s, int row_begin,
+                     int row_end, int32_t *logits, hipStream_t stream);
 
 enum BiasMode {
     BIAS_NONE = 0,
     BIAS_BF16_VEC = 1,  // rows 16-byte aligned: 16-byte loads, prefetched one block ahead
     BIAS_BF16_ANY = 2,  // any alignment: element loads
     BIAS_F32_VEC = 3,
-    BIAS_F32_ANY = 4
+    BIAS_F32_ANY = 4,
+    BIAS_BF16_LDS = 5   // rows 16-byte aligned, N % 8 == 0: tile staged global -> LDS asynchronously
 };
 
 struct FusedParams {
@@ -99,11 +137,9 @@ struct FusedParams {
     float scale;
     uint16_t *out;
     Strides3 os;
-    const int8_t *k8;
-    const int8_t *vt8;
-    const int *cs128;
+    const char *img;     // block images
     const float *delta;
-    int B, H, N, d, nblk, npad, nrb, total_wg;
+    int B, H, N, d, nblk, nrb, total_wg;
 };
 
 // Defined (and explicitly instantiated) in fused_dk<DK>.hip, DK = ceil(d / 32).

@@ -1,21 +1,34 @@
 // The fused loop of Alg. 1 for one (batch, head, 128-query block) per
-// workgroup: QK logits on the int8 matrix cores, scale + bias (Eq. 6), online
+// workgroup: QK logits on the matrix cores, scale + bias (Eq. 6), online
 // softmax, unsigned 8-bit P, int8 P.V with int32 accumulation, fp32 carry.
 //
 // One wave owns 32 query rows; a lane owns ONE query row and half of the keys
 // of every block (g = lane / 32 selects keys [64 g, 64 g + 64) of the block).
-// Per key block of BV = 128 keys:
-//   1. four 32x32 QK tiles -> 64 integer logits per lane (registers)
-//   2. S = alpha * I + b; block max (one cross-lane exchange with lane ^ 32)
-//   3. p = 255 * exp(S - m) through one FMA + v_exp_f32 in base 2; row sum;
-//      p rounded to a byte by v_cvt_pk_u8_f32
+// The vector ALU is the binding unit of this kernel, so the design removes
+// vector instructions wherever another unit can do the work.  Per key block of
+// BV = 128 keys:
+//   0. the next block's operand image is copied global -> LDS asynchronously
+//      (no staging registers, no LDS store instructions)
+//   1. T = I + b / alpha: the bias is unpacked, divided by the logit multiplier
+//      alpha = scale * mu_q * mu_k and handed to the FP4 MFMA as its accumulator
+//      input; the MFMA adds the exact integer logit I = s_i . t_j in fp32.
+//      (S of Eq. 6 is alpha * T; alpha > 0 after folding its sign into the Q
+//      operand, so maxima can be taken on T.)
+//   2. block max of T (one cross-lane exchange with lane ^ 32), running max m
+//   3. p = 255 * exp(S - m) = exp2(T * alpha*log2(e) + c) with one FMA and one
+//      v_exp_f32; row sum in fp32; p rounded to a byte by v_cvt_pk_u8_f32
+//      (Eq. 7, scale 1/255, relative to the running maximum as in Alg. 1)
 //   4. P.V: the int8 MFMA is signed x signed, so the operand is P - 128 and the
-//      accumulator starts from 128 * (column sums of the V block), which the V
-//      quantisation kernel precomputed: exact in int32
-//   5. O = exp(m_old - m_new) * O + int32 block result (Alg. 1 rescale line,
-//      read as a multiplication)
-// Final: O / (sum of 255 * P_hat) * delta_v (Alg. 1 last line; the factor 255
-// is already inside the row sum).
+//      accumulator starts from 128 * (column sums of the V block), precomputed
+//      by the V quantisation kernel: exact in int32.  The seed also carries the
+//      bit pattern of 1.5 * 2^23, so the finished int32 accumulator, read as
+//      fp32 bits, IS the float 1.5 * 2^23 + result: no int->float conversion.
+//   5. O = exp(m_old - m_new) * O + block result (Alg. 1's rescale line, read as
+//      a multiplication) is one FMA per output register; the 1.5 * 2^23 offsets
+//      accumulate as 1.5 * 2^23 * rho with rho = sum of the rescale products,
+//      tracked per row and subtracted once at the end.
+// Final: (O - 1.5*2^23*rho) / (sum of 255 * P_hat) * delta_v (Alg. 1 last line;
+// the factor 255 is already inside the row sum).
 #pragma once
 
 #include "attn_tiles.h"
@@ -36,9 +49,15 @@ __device__ __forceinline__ unsigned f32_to_bf16_rne(float f) {
 
 template <int DK, int MODE>
 __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedParams p) {
-    using TL = Tiles<DK>;
+    using L = Image<DK>;
     constexpr int DKP = 32 * DK;
-    __shared__ __attribute__((aligned(16))) TL tiles[2];
+    constexpr int DK2 = L::DK2;
+    // Two separate arrays (not one [2][..]) so that the compiler can tell the
+    // buffer being filled from the buffer being read.
+    __shared__ __attribute__((aligned(1024))) char bufA[L::BYTES];
+    __shared__ __attribute__((aligned(1024))) char bufB[L::BYTES];
+    // BIAS_BF16_LDS: wave-private staging of the wave's 32 x 128 bias tile (8 KiB per wave)
+    __shared__ __attribute__((aligned(1024))) char biasbuf[MODE == BIAS_BF16_LDS ? 4 * 8192 : 1024];
 
     // Workgroup -> work item.  Consecutive workgroup ids go to different XCDs, so
     // the id is first turned into (xcd, slot) and work items that share a bias
@@ -58,40 +77,22 @@ __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedPara
     const int q = rb * BR + wave * ROWS_PER_WAVE + m;  // this lane's query row
     const int qc = min(q, N - 1);                      // clamped for loads
 
+    // Logit multiplier alpha of Eq. 6.  Its sign goes into the Q operand and a
+    // vanishing alpha clears the Q operand, so that the loop can assume alpha > 0.
     float alpha = p.scale;
     if (p.mu_q) alpha *= p.mu_q[bh];
     if (p.mu_k) alpha *= p.mu_k[bh];
+    const bool a_zero = fabsf(alpha) < 1e-30f;
+    const bool a_neg = alpha < 0.0f;
+    const float a_abs = a_zero ? 1.0f : fabsf(alpha);
+    const float inv_alpha = 1.0f / a_abs;
+    const float a2 = a_abs * LOG2E_F;  // exponent multiplier in base 2
 
-    v4i qB[DK];
-    load_q_operand<DK>(p.q_bits + ((int64_t)bh * N + qc) * DK, d, g, qB);
+    v4i qB[DK2];
+    load_q_operand<DK2>(p.q_bits + ((int64_t)bh * N + qc) * ((d + 31) / 32), (d + 31) / 32, d, g,
+                        a_neg, a_zero, qB);
 
-    const int8_t *k8h = p.k8 + (int64_t)bh * p.npad * DKP;
-    const int8_t *vth = p.vt8 + (int64_t)bh * DKP * p.npad;
-    const int *csh = p.cs128 + (int64_t)bh * p.nblk * DKP;
-
-    // ---- global -> register -> LDS staging of one key/value block ----------
-    u4v kreg[DK], vreg[DK];
-    v4i csreg = {0, 0, 0, 0};
-#define BINATTN_LOAD_BLOCK(blk)                                                                   \
-    do {                                                                                          \
-        load_k_regs<DK>(k8h, (blk), kreg);                                                        \
-        _Pragma("unroll") for (int i_ = 0; i_ < DK; ++i_) {                                       \
-            const int ch_ = threadIdx.x + FUSED_THREADS * i_;                                     \
-            vreg[i_] = *reinterpret_cast<const u4v *>(vth + (int64_t)(ch_ >> 3) * p.npad +      \
-                                                        (blk) * BV + 16 * (ch_ & 7));             \
-        }                                                                                         \
-        if (threadIdx.x < DKP / 4)                                                                \
-            csreg = *reinterpret_cast<const v4i *>(csh + (int64_t)(blk) * DKP + 4 * threadIdx.x); \
-    } while (0)
-#define BINATTN_STORE_BLOCK(T_)                                                                   \
-    do {                                                                                          \
-        store_k_regs<DK>((T_), kreg);                                                             \
-        _Pragma("unroll") for (int i_ = 0; i_ < DK; ++i_) {                                       \
-            const int ch_ = threadIdx.x + FUSED_THREADS * i_;                                     \
-            *reinterpret_cast<u4v *>((T_).vt + (ch_ >> 3) * TL::VP + 16 * (ch_ & 7)) = vreg[i_]; \
-        }                                                                                         \
-        if (threadIdx.x < DKP / 4) *reinterpret_cast<v4i *>((T_).cs + 4 * threadIdx.x) = csreg;  \
-    } while (0)
+    const char *imgs = p.img + (int64_t)bh * p.nblk * L::BYTES;
 
     // ---- bias row of this lane ------------------------------------------------
     const int bsb = (MODE == BIAS_F32_VEC || MODE == BIAS_F32_ANY) ? 4 : 2;  // bytes per element
@@ -99,122 +100,161 @@ __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedPara
     if (MODE != BIAS_NONE)
         brow = static_cast<const char *>(p.bias) +
                ((int64_t)b * p.bs.b + (int64_t)h * p.bs.h + (int64_t)qc * p.bs.n) * bsb;
-    uint4 braw[8];  // BIAS_BF16_VEC: the 64 bias values of the current block
+    // BIAS_BF16_LDS: the tile is fetched with full-cache-line requests (8 lanes cover the
+    // 128 bytes of one row segment) straight into LDS.  Copy instruction (rg, gh) moves rows
+    // 8 rg + [0, 8) x keys 64 gh + [0, 64); lane 8 r + s fetches 16-byte chunk (s ^ r) of row
+    // r, so that chunk c of row r lands at 128 r + 16 (c ^ r): the later 16-byte reads of 8
+    // consecutive rows at one chunk index hit 8 different bank groups.
+    char *myb = biasbuf + (MODE == BIAS_BF16_LDS ? wave * 8192 : 0);
+    const char *bsrc[4] = {nullptr, nullptr, nullptr, nullptr};
+    const int dma_r = lane >> 3, dma_c = (lane & 7) ^ (lane >> 3);
+    if (MODE == BIAS_BF16_LDS) {
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+            const int row = min(rb * BR + wave * ROWS_PER_WAVE + 8 * rg + dma_r, N - 1);
+            bsrc[rg] = static_cast<const char *>(p.bias) +
+                       ((int64_t)b * p.bs.b + (int64_t)h * p.bs.h + (int64_t)row * p.bs.n) * 2 + 16 * dma_c;
+        }
+    }
+    auto dma_bias = [&](int blk) {
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg)
+#pragma unroll
+            for (int gh = 0; gh < 2; ++gh) {
+                const int key0 = blk * BV + 64 * gh + 8 * dma_c;
+                if (key0 + 8 <= N)
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void *)(bsrc[rg] + (blk * BV + 64 * gh) * 2),
+                        (__attribute__((address_space(3))) void *)(myb + (rg * 2 + gh) * 1024), 16, 0, 0);
+            }
+    };
+    u4v braw[8];  // BIAS_BF16_VEC: the 64 bias values of the block, prefetched
     auto load_bias_vec = [&](int blk) {
         const int k0 = blk * BV + 64 * g;
         const uint16_t *src = reinterpret_cast<const uint16_t *>(brow) + k0;
         if (blk * BV + BV <= N) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) braw[i] = *reinterpret_cast<const uint4 *>(src + 8 * i);
+            for (int i = 0; i < 8; ++i) braw[i] = *reinterpret_cast<const u4v *>(src + 8 * i);
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 if (k0 + 8 * i + 8 <= N) {
-                    braw[i] = *reinterpret_cast<const uint4 *>(src + 8 * i);
+                    braw[i] = *reinterpret_cast<const u4v *>(src + 8 * i);
                 } else {
                     unsigned e[8];
 #pragma unroll
                     for (int j = 0; j < 8; ++j) e[j] = (k0 + 8 * i + j < N) ? src[8 * i + j] : 0u;
-                    braw[i] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16),
-                                         e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+                    braw[i] = u4v{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16),
+                                  e[6] | (e[7] << 16)};
                 }
             }
         }
     };
-    // bias of tile t for this lane: keys blk*BV + 64 g + 16 t + [0, 16)
-    auto bias_tile = [&](int blk, int t, float bt[16]) {
+    // accumulator input of QK tile t: bias / alpha for keys blk*BV + 64 g + 16 t + [0, 16)
+    auto bias_tile = [&](int blk, int t) -> v16f {
         const int k0 = blk * BV + 64 * g + 16 * t;
+        v16f bt;
         if (MODE == BIAS_NONE) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) bt[r] = 0.0f;
         } else if (MODE == BIAS_BF16_VEC) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                const uint4 w = braw[2 * t + i];
-                const unsigned dw[4] = {w.x, w.y, w.z, w.w};
+                const u4v w = braw[2 * t + i];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    bt[8 * i + 2 * j] = bf16_lo(dw[j]);
-                    bt[8 * i + 2 * j + 1] = bf16_hi(dw[j]);
+                    bt[8 * i + 2 * j] = bf16_lo(w[j]) * inv_alpha;
+                    bt[8 * i + 2 * j + 1] = bf16_hi(w[j]) * inv_alpha;
+                }
+            }
+        } else if (MODE == BIAS_BF16_LDS) {
+            const char *row = myb + ((m >> 3) * 2 + g) * 1024 + 128 * (m & 7);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const u4v w = *reinterpret_cast<const u4v *>(row + 16 * ((2 * t + i) ^ (m & 7)));
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    bt[8 * i + 2 * j] = bf16_lo(w[j]) * inv_alpha;
+                    bt[8 * i + 2 * j + 1] = bf16_hi(w[j]) * inv_alpha;
                 }
             }
         } else if (MODE == BIAS_BF16_ANY) {
             const uint16_t *src = reinterpret_cast<const uint16_t *>(brow) + k0;
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                bt[r] = (k0 + r < N) ? __uint_as_float((unsigned)src[r] << 16) : 0.0f;
+                bt[r] = (k0 + r < N) ? __uint_as_float((unsigned)src[r] << 16) * inv_alpha : 0.0f;
         } else if (MODE == BIAS_F32_VEC) {
             const float *src = reinterpret_cast<const float *>(brow) + k0;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 if (k0 + 4 * i + 4 <= N) {
                     const float4 w = *reinterpret_cast<const float4 *>(src + 4 * i);
-                    bt[4 * i] = w.x; bt[4 * i + 1] = w.y; bt[4 * i + 2] = w.z; bt[4 * i + 3] = w.w;
+                    bt[4 * i] = w.x * inv_alpha; bt[4 * i + 1] = w.y * inv_alpha;
+                    bt[4 * i + 2] = w.z * inv_alpha; bt[4 * i + 3] = w.w * inv_alpha;
                 } else {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) bt[4 * i + j] = (k0 + 4 * i + j < N) ? src[4 * i + j] : 0.0f;
+                    for (int j = 0; j < 4; ++j)
+                        bt[4 * i + j] = (k0 + 4 * i + j < N) ? src[4 * i + j] * inv_alpha : 0.0f;
                 }
             }
         } else {
             const float *src = reinterpret_cast<const float *>(brow) + k0;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) bt[r] = (k0 + r < N) ? src[r] : 0.0f;
+            for (int r = 0; r < 16; ++r) bt[r] = (k0 + r < N) ? src[r] * inv_alpha : 0.0f;
         }
+        return bt;
     };
 
-    // ---- prologue ---------------------------------------------------------------
-    BINATTN_LOAD_BLOCK(0);
-    if (MODE == BIAS_BF16_VEC) load_bias_vec(0);
-    BINATTN_STORE_BLOCK(tiles[0]);
-    __syncthreads();
-
-    float m_run = -INFINITY;  // running row maximum (Alg. 1: m)
+    float m_run = -INFINITY;  // running row maximum, in units of T = S / alpha
     float l_run = 0.0f;       // running sum of 255 * exp(S - m) over this lane's keys
-    float Of[DK][16];         // fp32 carry of the output, channel 32cb + 8(r/4) + 4g + r%4
+    float rho = 0.0f;         // running sum of rescale products (see step 5 above)
+    float Of[DK][16];         // output carry, channel 32 cb + 8 (r/4) + 4 g + r % 4
 #pragma unroll
     for (int cb = 0; cb < DK; ++cb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) Of[cb][r] = 0.0f;
 
-    for (int it = 0; it < p.nblk; ++it) {
+    // One key/value block: compute on `cur`, prefetch block it + 1 into `nxt`.
+    auto step = [&](int it, const char *cur, char *nxt) {
         const bool more = it + 1 < p.nblk;
-        if (more) BINATTN_LOAD_BLOCK(it + 1);
-        const TL &T = tiles[it & 1];
+        if (more) dma_image<DK>(imgs + (int64_t)(it + 1) * L::BYTES, nxt, wave, lane);
 
-        // 1-2. logits of the block: S = alpha * (s_i . t_j) + b_ij  (Eq. 6)
-        float S[KT][16];
+        // 1. T = I + b / alpha
+        v16f T[KT];
 #pragma unroll
-        for (int t = 0; t < KT; ++t) {
-            const v16i acc = qk_tile<DK>(T, t, m, g, qB);
-            float bt[16];
-            bias_tile(it, t, bt);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) S[t][r] = fmaf((float)acc[r], alpha, bt[r]);
+        for (int t = 0; t < KT; ++t) T[t] = qk_tile<DK>(cur, t, m, g, qB, bias_tile(it, t));
+        if (MODE == BIAS_BF16_VEC && more) {
+            __builtin_amdgcn_sched_barrier(0);  // keep the prefetch behind the last use of braw
+            load_bias_vec(it + 1);
         }
-        if (MODE == BIAS_BF16_VEC && more) load_bias_vec(it + 1);
+        if (MODE == BIAS_BF16_LDS && more) {
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this block's tile has been read
+            dma_bias(it + 1);                                   // refill the wave's region
+        }
         if (it * BV + BV > N) {  // ragged last block: keys beyond N never count
 #pragma unroll
             for (int t = 0; t < KT; ++t)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    if (it * BV + 64 * g + 16 * t + r >= N) S[t][r] = -INFINITY;
+                    if (it * BV + 64 * g + 16 * t + r >= N) T[t][r] = -INFINITY;
         }
 
-        // running maximum (Alg. 1: m_ij = max(m_i,j-1, rowmax S_ij))
-        float mx = S[0][0];
+        // 2. running maximum (Alg. 1: m_ij = max(m_i,j-1, rowmax S_ij))
+        float mx = T[0][0];
 #pragma unroll
         for (int t = 0; t < KT; ++t)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[t][r]);
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, T[t][r]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float m_new = fmaxf(m_run, mx);
         const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;  // whole row masked so far
-        const float resc = __builtin_amdgcn_exp2f((m_run - m_use) * LOG2E_F);  // e^{m_old - m_new}
-        const float cexp = LOG2_255_F - m_use * LOG2E_F;
+        const float resc = __builtin_amdgcn_exp2f((m_run - m_use) * a2);  // e^{m_old - m_new}
+        const float cexp = LOG2_255_F - m_use * a2;
         m_run = m_new;
 
-        // 3. p = 255 * exp(S - m), its row sum, and the byte codes (Eq. 7, scale 1/255)
-        float lsum = 0.0f;
+        // 3. p = 255 * exp(S - m), its row sum, and the byte codes
+        float ls0 = 0.0f, ls1 = 0.0f;
         v4i pk[KT];
 #pragma unroll
         for (int t = 0; t < KT; ++t) {
@@ -223,40 +263,54 @@ __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedPara
                 unsigned w = 0;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const float pe = __builtin_amdgcn_exp2f(fmaf(S[t][4 * i + j], LOG2E_F, cexp));
-                    lsum += pe;
+                    const float pe = __builtin_amdgcn_exp2f(fmaf(T[t][4 * i + j], a2, cexp));
+                    if (j & 1) ls1 += pe; else ls0 += pe;
                     w = __builtin_amdgcn_cvt_pk_u8_f32(pe, j, w);
                 }
                 pk[t][i] = (int)(w ^ 0x80808080u);  // code - 128 as signed bytes
             }
         }
-        l_run = fmaf(l_run, resc, lsum);
+        l_run = fmaf(l_run, resc, ls0 + ls1);
+        rho = fmaf(rho, resc, 1.0f);
 
-        // 4-5. O = e^{m_old - m_new} O + P~ . V~   (int8 MFMA, int32 accumulate)
+        // 4-5. O = e^{m_old - m_new} O + P~ . V~
 #pragma unroll
         for (int cb = 0; cb < DK; ++cb) {
             v16i acc;
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                const int4 c4 = *reinterpret_cast<const int4 *>(T.cs + 32 * cb + 8 * q4 + 4 * g);
-                acc[4 * q4] = c4.x; acc[4 * q4 + 1] = c4.y; acc[4 * q4 + 2] = c4.z; acc[4 * q4 + 3] = c4.w;
+                const v4i c4 = *reinterpret_cast<const v4i *>(cur + L::CS_OFF + 4 * (32 * cb + 8 * q4 + 4 * g));
+                acc[4 * q4] = c4[0]; acc[4 * q4 + 1] = c4[1]; acc[4 * q4 + 2] = c4[2]; acc[4 * q4 + 3] = c4[3];
             }
 #pragma unroll
             for (int t = 0; t < KT; ++t) {
-                const v4i a = *reinterpret_cast<const v4i *>(T.vt + (32 * cb + m) * TL::VP + 64 * g + 16 * t);
+                const v4i a = *reinterpret_cast<const v4i *>(cur + L::V_OFF + (32 * cb + m) * L::VP + 64 * g + 16 * t);
                 acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pk[t], acc, 0, 0, 0);
             }
 #pragma unroll
-            for (int r = 0; r < 16; ++r) Of[cb][r] = fmaf(Of[cb][r], resc, (float)acc[r]);
+            for (int r = 0; r < 16; ++r) Of[cb][r] = fmaf(Of[cb][r], resc, __int_as_float(acc[r]));
         }
 
-        if (more) BINATTN_STORE_BLOCK(tiles[(it + 1) & 1]);
-        __syncthreads();
+        wait_vmem();      // this wave's share of the next image (and its bias prefetch) has landed
+        __syncthreads();  // everyone is done with `cur`, and `nxt` is complete
+    };
+
+    // ---- prologue ---------------------------------------------------------------
+    dma_image<DK>(imgs, bufA, wave, lane);
+    if (MODE == BIAS_BF16_VEC) load_bias_vec(0);
+    if (MODE == BIAS_BF16_LDS) dma_bias(0);
+    wait_vmem();
+    __syncthreads();
+
+    for (int it = 0; it < p.nblk; it += 2) {
+        step(it, bufA, bufB);
+        if (it + 1 < p.nblk) step(it + 1, bufB, bufA);
     }
 
-    // ---- epilogue: O / (255 l) * delta_v, bf16 store ----------------------------
+    // ---- epilogue: (O - magic * rho) / (255 l) * delta_v, bf16 store -------------
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     const float inv = 1.0f / l_tot;
+    const float off = PV_MAGIC_F * rho;
     if (q < N) {
         uint16_t *orow = p.out + (int64_t)b * p.os.b + (int64_t)h * p.os.h + (int64_t)q * p.os.n;
         const float *dl = p.delta + (int64_t)bh * DKP;
@@ -267,18 +321,15 @@ __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedPara
                 const int c = 32 * cb + 8 * q4 + 4 * g;
                 if (c < d) {
                     const float4 d4 = *reinterpret_cast<const float4 *>(dl + c);
-                    const unsigned y0 = f32_to_bf16_rne(Of[cb][4 * q4 + 0] * inv * d4.x);
-                    const unsigned y1 = f32_to_bf16_rne(Of[cb][4 * q4 + 1] * inv * d4.y);
-                    const unsigned y2 = f32_to_bf16_rne(Of[cb][4 * q4 + 2] * inv * d4.z);
-                    const unsigned y3 = f32_to_bf16_rne(Of[cb][4 * q4 + 3] * inv * d4.w);
+                    const unsigned y0 = f32_to_bf16_rne((Of[cb][4 * q4 + 0] - off) * inv * d4.x);
+                    const unsigned y1 = f32_to_bf16_rne((Of[cb][4 * q4 + 1] - off) * inv * d4.y);
+                    const unsigned y2 = f32_to_bf16_rne((Of[cb][4 * q4 + 2] - off) * inv * d4.z);
+                    const unsigned y3 = f32_to_bf16_rne((Of[cb][4 * q4 + 3] - off) * inv * d4.w);
                     *reinterpret_cast<uint2 *>(orow + c) = make_uint2(y0 | (y1 << 16), y2 | (y3 << 16));
                 }
             }
     }
 }
-
-#undef BINATTN_LOAD_BLOCK
-#undef BINATTN_STORE_BLOCK
 
 template <int DK>
 int launch_fused_dk(const FusedParams &p, int mode, hipStream_t stream) {
@@ -286,6 +337,7 @@ int launch_fused_dk(const FusedParams &p, int mode, hipStream_t stream) {
     switch (mode) {
 #define CASE(M) case M: hipLaunchKernelGGL((fused_kernel<DK, M>), grid, block, 0, stream, p); break;
         CASE(BIAS_NONE) CASE(BIAS_BF16_VEC) CASE(BIAS_BF16_ANY) CASE(BIAS_F32_VEC) CASE(BIAS_F32_ANY)
+        CASE(BIAS_BF16_LDS)
 #undef CASE
         default: return BINATTN_ERR_DTYPE;
     }

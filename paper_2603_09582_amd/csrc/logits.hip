@@ -1,7 +1,10 @@
-// Integer logits I_ij = s_i . t_j (Sec. 4.1) exported to memory, two ways:
+// Integer logits I_ij = s_i . t_j (Sec. 4.1) exported to memory, three ways:
 //   * vector-ALU form: d - 2 * popcount(q XOR k) straight from the sign words
-//   * matrix-core form: the +-1 int8 MFMA tile routine of the fused kernel
-// Both are exact; they exist so that the two can be compared and timed.
+//   * int8 matrix-core form: +-1 bytes on v_mfma_i32_32x32x32_i8
+//   * FP4 matrix-core form: the QK tile routine of the fused kernel
+//     (v_mfma_f32_32x32x64_f8f6f4 on +-1.0 FP4 codes, exact in fp32)
+// All are exact; they exist so that the forms can be compared and timed, and so
+// that the fused kernel's tile routine is checked bit for bit.
 #include "attn_tiles.h"
 
 namespace binattn {
@@ -22,35 +25,102 @@ __global__ void logits_popcount_kernel(const uint32_t *__restrict__ q_bits,
     logits[(int64_t)bh * nrows * N + i] = d - 2 * ham;
 }
 
-// One workgroup per (head, 128-row block); loops over key blocks.
+// FP4 form.  One workgroup per (head, 128-row block); loops over key blocks,
+// reading the operand images binattn's key preparation wrote.
 template <int DK>
-__global__ __launch_bounds__(FUSED_THREADS) void logits_mfma_kernel(
-    const uint32_t *__restrict__ q_bits, const int8_t *__restrict__ k8, int N, int d, int nblk,
+__global__ __launch_bounds__(FUSED_THREADS) void logits_fp4_kernel(
+    const uint32_t *__restrict__ q_bits, const char *__restrict__ img, int N, int d, int nblk,
     int row_begin, int nrows, int nrb, int32_t *__restrict__ logits) {
-    __shared__ __attribute__((aligned(16))) Tiles<DK> T;
+    using L = Image<DK>;
+    __shared__ __attribute__((aligned(1024))) char buf[L::BYTES];
     const int rb = blockIdx.x % nrb, bh = blockIdx.x / nrb;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 31, g = lane >> 5;
     const int r = rb * BR + wave * ROWS_PER_WAVE + m;  // row inside [0, nrows)
     const int q = min(row_begin + r, N - 1);
-    v4i qB[DK];
-    load_q_operand<DK>(q_bits + ((int64_t)bh * N + q) * DK, d, g, qB);
-    const int8_t *k8h = k8 + (int64_t)bh * nblk * BV * (32 * DK);
+    const int W = (d + 31) / 32;
+    v4i qB[L::DK2];
+    load_q_operand<L::DK2>(q_bits + ((int64_t)bh * N + q) * W, W, d, g, false, false, qB);
+    const char *imgs = img + (int64_t)bh * nblk * L::BYTES;
     int32_t *orow = logits + ((int64_t)bh * nrows + r) * N;
     for (int blk = 0; blk < nblk; ++blk) {
-        u4v kreg[DK];
-        load_k_regs<DK>(k8h, blk, kreg);
         __syncthreads();  // previous block's reads are done
-        store_k_regs<DK>(T, kreg);
+        dma_image<DK>(imgs + (int64_t)blk * L::BYTES, buf, wave, lane);
+        wait_vmem();
         __syncthreads();
 #pragma unroll
         for (int t = 0; t < KT; ++t) {
-            const v16i acc = qk_tile<DK>(T, t, m, g, qB);
+            const v16f zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+            const v16f acc = qk_tile<DK>(buf, t, m, g, qB, zero);
             const int k0 = blk * BV + 64 * g + 16 * t;
             if (r < nrows) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
-                    if (k0 + i < N) orow[k0 + i] = acc[i];
+                    if (k0 + i < N) orow[k0 + i] = (int32_t)acc[i];
+            }
+        }
+    }
+}
+
+// 4 sign bits -> 4 bytes holding +1 (bit set) or -1 (bit clear).
+__device__ __forceinline__ unsigned pm1_bytes(unsigned nib) {
+    unsigned x = (nib * 0x00204081u) & 0x01010101u;
+    return x | ((x ^ 0x01010101u) * 0xFFu);
+}
+
+// int8 form: +-1 bytes are expanded from the sign words inside the kernel.
+// Lane layout as in the fused kernel (keys on the A side, one query per lane).
+template <int DK>
+__global__ __launch_bounds__(FUSED_THREADS) void logits_i8_kernel(
+    const uint32_t *__restrict__ q_bits, const uint32_t *__restrict__ k_bits, int N, int d,
+    int nblk, int row_begin, int nrows, int nrb, int32_t *__restrict__ logits) {
+    constexpr int KP = 32 * DK + 16;
+    __shared__ __attribute__((aligned(16))) char k8[BV * KP];
+    const int rb = blockIdx.x % nrb, bh = blockIdx.x / nrb;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 31, g = lane >> 5;
+    const int r = rb * BR + wave * ROWS_PER_WAVE + m;
+    const int q = min(row_begin + r, N - 1);
+    v4i qB[DK];
+#pragma unroll
+    for (int s = 0; s < DK; ++s) {
+        const unsigned half = (q_bits[((int64_t)bh * N + q) * DK + s] >> (16 * g)) & 0xffffu;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            qB[s][i] = (32 * s + 16 * g + 4 * i < d) ? (int)pm1_bytes((half >> (4 * i)) & 0xFu) : 0;
+    }
+    const uint32_t *kb = k_bits + (int64_t)bh * N * DK;
+    int32_t *orow = logits + ((int64_t)bh * nrows + r) * N;
+    for (int blk = 0; blk < nblk; ++blk) {
+        __syncthreads();
+        // row `pos` of the tile holds key blk*BV + pos (natural order)
+        for (int i = threadIdx.x; i < BV * DK; i += FUSED_THREADS) {
+            const int pos = i / DK, w = i % DK;
+            const int key = blk * BV + pos;
+            const uint32_t word = key < N ? kb[(int64_t)key * DK + w] : 0u;
+#pragma unroll
+            for (int n = 0; n < 8; ++n) {
+                const bool live = key < N && 32 * w + 4 * n < d;
+                *reinterpret_cast<unsigned *>(k8 + pos * KP + 32 * w + 4 * n) =
+                    live ? pm1_bytes((word >> (4 * n)) & 0xFu) : 0u;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < KT; ++t) {
+            v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int s = 0; s < DK; ++s) {
+                const v4i a = *reinterpret_cast<const v4i *>(k8 + (32 * t + m) * KP + 32 * s + 16 * g);
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, qB[s], acc, 0, 0, 0);
+            }
+            // register i of lane group g is tile row 8 (i/4) + 4 g + (i%4)
+            if (r < nrows) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int key = blk * BV + 32 * t + 8 * (i >> 2) + 4 * g + (i & 3);
+                    if (key < N) orow[key] = acc[i];
+                }
             }
         }
     }
@@ -66,14 +136,30 @@ int launch_logits_popcount(const uint32_t *q_bits, const uint32_t *k_bits, const
     return check_launch();
 }
 
-int launch_logits_mfma(const uint32_t *q_bits, const int8_t *k8, const Shape &s, int row_begin,
-                       int row_end, int32_t *logits, hipStream_t stream) {
+int launch_logits_fp4(const uint32_t *q_bits, const char *ws, const Workspace &w, const Shape &s,
+                      int row_begin, int row_end, int32_t *logits, hipStream_t stream) {
     const int nrows = row_end - row_begin;
     if (nrows == 0) return BINATTN_OK;
     const int nrb = (nrows + BR - 1) / BR;
     const dim3 grid((unsigned)nrb * s.BH), block(FUSED_THREADS);
     switch (s.DK) {
-#define CASE(K) case K: hipLaunchKernelGGL(logits_mfma_kernel<K>, grid, block, 0, stream, q_bits, k8, \
+#define CASE(K) case K: hipLaunchKernelGGL(logits_fp4_kernel<K>, grid, block, 0, stream, q_bits, \
+                                           ws + w.img, s.N, s.d, s.nblk, row_begin, nrows, nrb, logits); break;
+        CASE(1) CASE(2) CASE(3) CASE(4)
+#undef CASE
+        default: return BINATTN_ERR_SHAPE;
+    }
+    return check_launch();
+}
+
+int launch_logits_i8(const uint32_t *q_bits, const uint32_t *k_bits, const Shape &s, int row_begin,
+                     int row_end, int32_t *logits, hipStream_t stream) {
+    const int nrows = row_end - row_begin;
+    if (nrows == 0) return BINATTN_OK;
+    const int nrb = (nrows + BR - 1) / BR;
+    const dim3 grid((unsigned)nrb * s.BH), block(FUSED_THREADS);
+    switch (s.DK) {
+#define CASE(K) case K: hipLaunchKernelGGL(logits_i8_kernel<K>, grid, block, 0, stream, q_bits, k_bits, \
                                            s.N, s.d, s.nblk, row_begin, nrows, nrb, logits); break;
         CASE(1) CASE(2) CASE(3) CASE(4)
 #undef CASE

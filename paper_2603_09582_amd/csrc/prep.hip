@@ -1,19 +1,25 @@
-// Operand preparation for the fused kernel:
-//   * K sign words -> +-1 int8 rows in the order the QK MFMA tile wants them
+// Operand preparation for the fused kernel.  Both kernels write straight into
+// the per-block operand images (see Image<DK>) that the attention kernel copies
+// into LDS:
+//   * K sign words -> FP4 codes of +-1, rows in the order the QK MFMA tile
+//     wants them
 //   * psi of Alg. 1 (Eq. 7): per-channel absmax of V, delta_v, signed 8-bit
-//     codes stored channel-major, and 128 * column sums per key block (the
-//     correction term of the signed P operand, see fused.hip)
-// All three are HBM-bound streaming kernels.
+//     codes stored channel-major, and the accumulator seed of the P.V
+//     contraction (128 * column sums per key block, see fused_impl.h)
+// All are HBM-bound streaming kernels.
 #include "binattn_internal.h"
 
 namespace binattn {
 
 constexpr int PREP_THREADS = 256;
+typedef unsigned u4 __attribute__((ext_vector_type(4)));
 
-// 4 sign bits -> 4 bytes holding +1 (bit set) or -1 (bit clear).
-__device__ __forceinline__ unsigned expand_nibble_pm1(unsigned nib) {
-    unsigned x = (nib * 0x00204081u) & 0x01010101u;  // bit i -> byte i
-    return x | ((x ^ 0x01010101u) * 0xFFu);          // 0x01 where set, 0xFF where clear
+// 8 sign bits -> 8 FP4 (e2m1) nibbles: +1.0 (0x2) where set, -1.0 (0xA) where clear.
+__device__ __forceinline__ unsigned fp4_pm1_bits8(unsigned b) {
+    unsigned sp = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sp |= ((b >> i) & 1u) << (4 * i);
+    return 0xAAAAAAAAu - (sp << 3);
 }
 
 // Row position inside a key block <-> key offset.  The fused kernel's lane
@@ -28,25 +34,27 @@ __device__ __forceinline__ int key_of_position(int pos) {
     return 64 * g + 16 * t + r;
 }
 
+// One thread per (row position, sign word): 32 channels -> 16 bytes of FP4 codes.
 __global__ __launch_bounds__(PREP_THREADS) void expand_k_kernel(const uint32_t *__restrict__ k_bits,
                                                                 int N, int d, int W, int nblk,
-                                                                int8_t *__restrict__ k8) {
+                                                                int img_bytes, int KP,
+                                                                char *__restrict__ img) {
     const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
-    const int DKP = 32 * W;
+    const int W2 = 2 * ((W + 1) / 2);  // words per row incl. the zero word that pads to 64 channels
     const uint32_t *kb = k_bits + (int64_t)bh * N * W;
-    int8_t *dst = k8 + ((int64_t)bh * nblk + blk) * BV * DKP;
-    for (int i = threadIdx.x; i < BV * W; i += PREP_THREADS) {
-        const int pos = i / W, w = i % W;
+    char *dst = img + ((int64_t)bh * nblk + blk) * img_bytes;
+    for (int i = threadIdx.x; i < BV * W2; i += PREP_THREADS) {
+        const int pos = i / W2, w = i % W2;
         const int key = blk * BV + key_of_position(pos);
-        const uint32_t word = key < N ? kb[(int64_t)key * W + w] : 0u;
-        const int valid = key < N ? d - 32 * w : 0;  // real channels in this word
-        uint32_t o[8];
+        const bool live = key < N && w < W;
+        const uint32_t word = live ? kb[(int64_t)key * W + w] : 0u;
+        const int valid = live ? d - 32 * w : 0;  // real channels in this word
+        u4 o;
+        unsigned *op = reinterpret_cast<unsigned *>(&o);
 #pragma unroll
-        for (int n = 0; n < 8; ++n)
-            o[n] = (4 * n < valid) ? expand_nibble_pm1((word >> (4 * n)) & 0xFu) : 0u;
-        uint4 *p = reinterpret_cast<uint4 *>(dst + (int64_t)pos * DKP + 32 * w);
-        p[0] = make_uint4(o[0], o[1], o[2], o[3]);
-        p[1] = make_uint4(o[4], o[5], o[6], o[7]);
+        for (int n = 0; n < 4; ++n)
+            op[n] = (8 * n < valid) ? fp4_pm1_bits8((word >> (8 * n)) & 0xFFu) : 0u;
+        *reinterpret_cast<u4 *>(dst + (int64_t)pos * KP + 16 * w) = o;
     }
 }
 
@@ -101,14 +109,13 @@ __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(const uint16_t *_
                                                                int nchunk, int nblk,
                                                                const float *__restrict__ amax,
                                                                float *__restrict__ delta,
-                                                               int8_t *__restrict__ vt8,
-                                                               int *__restrict__ cs128) {
+                                                               int img_bytes, int v_off, int cs_off,
+                                                               char *__restrict__ img) {
     constexpr int D = 8 * C16;
     constexpr int LDT = BV + 16;  // LDS row pitch in bytes
     __shared__ float sdelta[D];
     __shared__ __attribute__((aligned(16))) int8_t tile[128 * LDT];  // up to DKP = 128 rows
     const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
-    const int npad = nblk * BV;
     const int b = bh / H, h = bh % H;
     const uint16_t *vb = v + (int64_t)b * vs.b + (int64_t)h * vs.h;
 
@@ -141,35 +148,47 @@ __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(const uint16_t *_
     }
     __syncthreads();
 
-    int8_t *vt = vt8 + (int64_t)bh * DKP * npad;
+    char *dst = img + ((int64_t)bh * nblk + blk) * img_bytes;
     for (int i = threadIdx.x; i < DKP * (BV / 16); i += PREP_THREADS) {
         const int c = i / (BV / 16), part = i % (BV / 16);
-        const uint4 val = *reinterpret_cast<const uint4 *>(tile + c * LDT + 16 * part);
-        *reinterpret_cast<uint4 *>(vt + (int64_t)c * npad + j0 + 16 * part) = val;
+        const u4 val = *reinterpret_cast<const u4 *>(tile + c * LDT + 16 * part);
+        *reinterpret_cast<u4 *>(dst + v_off + c * LDT + 16 * part) = val;
     }
     if (threadIdx.x < DKP) {
         int sum = 0;
         for (int j = 0; j < BV; ++j) sum += (int)tile[threadIdx.x * LDT + j];
-        cs128[((int64_t)bh * nblk + blk) * DKP + threadIdx.x] = 128 * sum;
+        reinterpret_cast<int *>(dst + cs_off)[threadIdx.x] = PV_MAGIC_BITS + 128 * sum;
     }
 }
 
 // Codes and delta from the private layout into [B,H,N,d] / [B,H,d].
-__global__ void export_vq_kernel(const int8_t *__restrict__ vt8, const float *__restrict__ dl,
-                                 int N, int d, int DKP, int npad, int nper,
+__global__ void export_vq_kernel(const char *__restrict__ img, const float *__restrict__ dl, int N,
+                                 int d, int DKP, int nblk, int img_bytes, int v_off, int nper,
                                  int8_t *__restrict__ vq, float *__restrict__ delta) {
     const int bh = blockIdx.x / nper;
     const int64_t i = (int64_t)(blockIdx.x % nper) * blockDim.x + threadIdx.x;
     if (i < (int64_t)N * d) {
         const int n = (int)(i / d), c = (int)(i % d);
-        vq[(int64_t)bh * N * d + i] = vt8[((int64_t)bh * DKP + c) * npad + n];
+        const char *src = img + ((int64_t)bh * nblk + n / BV) * img_bytes + v_off;
+        vq[(int64_t)bh * N * d + i] = (int8_t)src[c * (BV + 16) + (n % BV)];
     }
     if (i < d) delta[(int64_t)bh * d + i] = dl[(int64_t)bh * DKP + i];
 }
 
-int launch_expand_k(const uint32_t *k_bits, const Shape &s, int8_t *k8, hipStream_t stream) {
+static void image_offsets(int DK, int *KP, int *v_off, int *cs_off) {
+    switch (DK) {
+#define CASE(K) case K: *KP = Image<K>::KP; *v_off = Image<K>::V_OFF; *cs_off = Image<K>::CS_OFF; break;
+        CASE(1) CASE(2) CASE(3) default: CASE(4)
+#undef CASE
+    }
+}
+
+int launch_expand_k(const uint32_t *k_bits, const Shape &s, char *ws, const Workspace &w,
+                    hipStream_t stream) {
+    int KP, v_off, cs_off;
+    image_offsets(s.DK, &KP, &v_off, &cs_off);
     hipLaunchKernelGGL(expand_k_kernel, dim3((unsigned)s.nblk * s.BH), dim3(PREP_THREADS), 0,
-                       stream, k_bits, s.N, s.d, s.W, s.nblk, k8);
+                       stream, k_bits, s.N, s.d, s.W, s.nblk, w.img_bytes, KP, ws + w.img);
     return check_launch();
 }
 
@@ -179,12 +198,13 @@ static void launch_quant_v_t(const void *v, Strides3 vs, const Shape &s, char *w
     const uint16_t *vp = static_cast<const uint16_t *>(v);
     float *amax = reinterpret_cast<float *>(ws + w.amax);
     float *delta = reinterpret_cast<float *>(ws + w.delta);
-    int8_t *vt8 = reinterpret_cast<int8_t *>(ws + w.vt8);
-    int *cs = reinterpret_cast<int *>(ws + w.cs128);
+    int KP, v_off, cs_off;
+    image_offsets(s.DK, &KP, &v_off, &cs_off);
     hipLaunchKernelGGL(v_absmax_kernel<C16>, dim3((unsigned)s.nchunk * s.BH), dim3(PREP_THREADS),
                        0, stream, vp, vs, s.H, s.N, s.DKP, s.nchunk, amax);
     hipLaunchKernelGGL(v_quant_kernel<C16>, dim3((unsigned)s.nblk * s.BH), dim3(PREP_THREADS), 0,
-                       stream, vp, vs, s.H, s.N, s.DKP, s.nchunk, s.nblk, amax, delta, vt8, cs);
+                       stream, vp, vs, s.H, s.N, s.DKP, s.nchunk, s.nblk, amax, delta, w.img_bytes,
+                       v_off, cs_off, ws + w.img);
 }
 
 int launch_quant_v(const void *v, Strides3 vs, const Shape &s, char *ws, const Workspace &w,
@@ -203,10 +223,11 @@ int launch_export_vq(const Shape &s, const char *ws, const Workspace &w, int8_t 
                      hipStream_t stream) {
     const int64_t total = (int64_t)s.N * s.d;
     const int nper = (int)((total + 255) / 256);
+    int KP, v_off, cs_off;
+    image_offsets(s.DK, &KP, &v_off, &cs_off);
     hipLaunchKernelGGL(export_vq_kernel, dim3((unsigned)nper * s.BH), dim3(256), 0, stream,
-                       reinterpret_cast<const int8_t *>(ws + w.vt8),
-                       reinterpret_cast<const float *>(ws + w.delta), s.N, s.d, s.DKP, s.npad,
-                       nper, vq, delta);
+                       ws + w.img, reinterpret_cast<const float *>(ws + w.delta), s.N, s.d, s.DKP,
+                       s.nblk, w.img_bytes, v_off, nper, vq, delta);
     return check_launch();
 }
 

@@ -92,7 +92,7 @@ def test_debug_entry_points_reject_bad_arguments():
     L = ba.lib()
     f = lambda **k: L.binattn_logits_debug(
         k.get("qb", FAKE), k.get("kb", FAKE), 1, 2, k.get("N", 16), k.get("d", 64), k.get("r0", 0),
-        k.get("r1", 16), k.get("out", FAKE), k.get("variant", 1), k.get("ws", FAKE),
+        k.get("r1", 16), k.get("out", FAKE), k.get("variant", 2), k.get("ws", FAKE),
         k.get("wsb", 1 << 30), None)
     assert f(qb=None) == -1 and f(out=None) == -1
     assert f(d=7) == -2

@@ -47,7 +47,8 @@ def small_inputs(B, H, N, d, seed, extra=""):
 
 
 SHAPES = [(1, 2, 1, 64), (1, 2, 2, 8), (2, 1, 63, 64), (1, 2, 64, 72), (1, 1, 65, 128), (1, 3, 129, 64),
-          (2, 2, 197, 64), (1, 2, 255, 72), (1, 1, 257, 16), (1, 2, 300, 104), (1, 1, 520, 32)]
+          (2, 2, 197, 64), (1, 2, 255, 72), (1, 1, 257, 16), (1, 2, 300, 104), (1, 1, 520, 32),
+          (1, 1, 256, 128), (1, 2, 136, 96), (2, 1, 384, 64)]
 
 
 @pytest.mark.parametrize("B,H,N,d", SHAPES)
@@ -108,7 +109,7 @@ def test_quant_v_codes_and_delta_exact(B, H, N, d):
             assert np.array_equal(vq[b, h].cpu().numpy(), wq)
 
 
-@pytest.mark.parametrize("variant", [ba.LOGITS_POPCOUNT, ba.LOGITS_MFMA_I8])
+@pytest.mark.parametrize("variant", [ba.LOGITS_POPCOUNT, ba.LOGITS_MFMA_I8, ba.LOGITS_MFMA_FP4])
 @pytest.mark.parametrize("B,H,N,d", SHAPES)
 def test_integer_logits_exact(B, H, N, d, variant):
     say(f"logits variant={variant} B={B} H={H} N={N} d={d}")
@@ -170,6 +171,19 @@ def test_forward_matches_oracle_bf16_bias(B, H, N, d):
     err = np.abs(got - alg)
     say(f"    vs Alg.1(Bv=128): max abs err {err.max():.3e}")
     assert np.all(err <= 2e-3 + 2 ** -7 * np.abs(alg))
+
+
+def test_forward_bf16_bias_padded_rows_odd_n():
+    # N = 197 inside rows padded to 200 elements: 16-byte aligned rows but a ragged row end,
+    # which takes the register-prefetch bias path with its guarded last chunk
+    B, H, N, d = 1, 2, 197, 64
+    x = small_inputs(B, H, N, d, 55)
+    store = torch.zeros(H, N, 200, dtype=torch.bfloat16, device="cuda")
+    store[:, :, :N] = dev(x.bias)
+    qb, kb, mq, mk = ba.pack_qk(dev(x.q), dev(x.k))
+    out = ba.forward(qb, kb, mq, mk, dev(x.v), store[:, :, :N], x.scale)
+    torch.cuda.synchronize()
+    check_close(gpu_out_f64(out), oracle_forward(x, x.bias)["O2"], "padded odd-N rows: out vs O2")
 
 
 @pytest.mark.parametrize("kind", ["none", "f32", "f32_per_batch", "bf16_per_batch", "bf16_padded_rows",
