@@ -77,8 +77,8 @@ const char *binattn_strerror(int code);
  *               (c & 31) of word (c >> 5) is 1 iff x[c] >= 0 under IEEE
  *               comparison (+0 and -0 give 1, NaN gives 0); unused bits are 0.
  *   mu_q, mu_k: out, float32 [B, H]: mean of |x| over the N*d elements of the
- *               head (Eq. 5 text).  Accumulated with float atomics, so the last
- *               bits may differ between runs.
+ *               head (Eq. 5 text).  For N > 2048 the sum goes through float
+ *               atomics, so the last bits may differ between runs.
  */
 int binattn_pack_qk(const void *q, const void *k, int B, int H, int N, int d,
                     const int64_t q_strides[3], const int64_t k_strides[3],
@@ -109,9 +109,10 @@ int binattn_prepare_kv(const uint32_t *k_bits, const void *v, const int64_t v_st
  *   mu_q, mu_k : float32 [B, H]; either may be NULL (taken as 1).
  *   bias       : [.., N, N] of bias_dtype, element strides bias_strides for
  *                (batch, head, row); a batch stride of 0 shares one bias over
- *                the batch.  May be NULL (no bias).  Rows need no particular
- *                alignment, but the fast load path needs a 16-byte aligned base
- *                and strides that keep every row 16-byte aligned.
+ *                the batch.  May be NULL (no bias).  Rows need only element
+ *                alignment; the fastest path (tiles staged through LDS) needs
+ *                bf16, a 16-byte aligned base, strides that keep every row
+ *                16-byte aligned, N a multiple of 8 and d <= 96.
  *   scale      : multiplies the +-1 inner product (1/sqrt(d) in Eq. 6); the
  *                effective multiplier is scale * mu_q[b,h] * mu_k[b,h].
  *   out        : bf16 [B, H, N, d], strides out_strides, rounded to nearest even

@@ -74,9 +74,7 @@ int binattn_pack_qk(const void *q, const void *k, int B, int H, int N, int d,
         !aligned(mu_q, 4) || !aligned(mu_k, 4))
         return BINATTN_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if ((rc = launch_zero_f32(mu_q, mu_k, s.BH, st)) != BINATTN_OK) return rc;
-    if ((rc = launch_pack(q, qs, s, q_bits, mu_q, st)) != BINATTN_OK) return rc;
-    return launch_pack(k, ks, s, k_bits, mu_k, st);
+    return launch_pack_qk(q, qs, k, ks, s, q_bits, k_bits, mu_q, mu_k, st);
 }
 
 int binattn_prepare_kv(const uint32_t *k_bits, const void *v, const int64_t v_strides[3], int B,
@@ -92,8 +90,7 @@ int binattn_prepare_kv(const uint32_t *k_bits, const void *v, const int64_t v_st
     if ((rc = check_workspace(workspace, workspace_bytes, w)) != BINATTN_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
-    if ((rc = launch_quant_v(v, vs, s, ws, w, st)) != BINATTN_OK) return rc;
-    return launch_expand_k(k_bits, s, ws, w, st);
+    return launch_prepare(v, vs, k_bits, s, ws, w, st);
 }
 
 int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k, const void *bias,
@@ -122,15 +119,13 @@ int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
         bs.b = bias_strides[0]; bs.h = bias_strides[1]; bs.n = bias_strides[2];
         const int esz = bias_dtype == BINATTN_BIAS_BF16 ? 2 : 4;
         if (!aligned(bias, esz)) return BINATTN_ERR_ALIGN;
-        const int per16 = 16 / esz;
-        const bool vec = aligned(bias, 16) && bs.b % per16 == 0 && bs.h % per16 == 0 && bs.n % per16 == 0;
         if (bias_dtype == BINATTN_BIAS_BF16) {
-            mode = vec ? BIAS_BF16_VEC : BIAS_BF16_ANY;
-            // LDS staging needs whole 16-byte chunks inside the row and LDS room for two
-            // workgroups per CU (d <= 96)
-            if (vec && N % 8 == 0 && s.DK <= 3) mode = BIAS_BF16_LDS;
+            // LDS staging needs 16-byte aligned rows made of whole 16-byte chunks, and LDS
+            // room for two workgroups per CU (d <= 96); everything else takes register loads.
+            const bool rows16 = aligned(bias, 16) && bs.b % 8 == 0 && bs.h % 8 == 0 && bs.n % 8 == 0;
+            mode = (rows16 && N % 8 == 0 && s.DK <= 3) ? BIAS_BF16_LDS : BIAS_BF16_VEC;
         } else {
-            mode = vec ? BIAS_F32_VEC : BIAS_F32_ANY;
+            mode = BIAS_F32_VEC;
         }
     }
     if ((rc = check_workspace(workspace, workspace_bytes, w)) != BINATTN_OK) return rc;
@@ -231,7 +226,7 @@ int binattn_quant_v_debug(const void *v, const int64_t v_strides[3], int B, int 
     if ((rc = check_workspace(workspace, workspace_bytes, w)) != BINATTN_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
-    if ((rc = launch_quant_v(v, vs, s, ws, w, st)) != BINATTN_OK) return rc;
+    if ((rc = launch_prepare(v, vs, nullptr, s, ws, w, st)) != BINATTN_OK) return rc;
     return launch_export_vq(s, ws, w, vq, delta, st);
 }
 

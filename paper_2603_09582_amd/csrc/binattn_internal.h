@@ -104,13 +104,13 @@ struct Strides3 {
 };
 
 // Launchers (each returns BINATTN_OK or BINATTN_ERR_LAUNCH).
-int launch_pack(const void *x, Strides3 xs, const Shape &s, uint32_t *bits, float *mu,
-                hipStream_t stream);
-int launch_zero_f32(float *a, float *b, int n, hipStream_t stream);
+int launch_pack_qk(const void *q, Strides3 qs, const void *k, Strides3 ks, const Shape &s,
+                   uint32_t *q_bits, uint32_t *k_bits, float *mu_q, float *mu_k,
+                   hipStream_t stream);
 int launch_expand_k(const uint32_t *k_bits, const Shape &s, char *ws, const Workspace &w,
                     hipStream_t stream);
-int launch_quant_v(const void *v, Strides3 vs, const Shape &s, char *ws, const Workspace &w,
-                   hipStream_t stream);
+int launch_prepare(const void *v, Strides3 vs, const uint32_t *k_bits, const Shape &s, char *ws,
+                   const Workspace &w, hipStream_t stream);
 int launch_export_vq(const Shape &s, const char *ws, const Workspace &w, int8_t *vq, float *delta,
                      hipStream_t stream);
 int launch_logits_popcount(const uint32_t *q_bits, const uint32_t *k_bits, const Shape &s,
@@ -122,10 +122,8 @@ int launch_logits_i8(const uint32_t *q_bits, const uint32_t *k_bits, const Shape
 
 enum BiasMode {
     BIAS_NONE = 0,
-    BIAS_BF16_VEC = 1,  // rows 16-byte aligned: 16-byte loads, prefetched one block ahead
-    BIAS_BF16_ANY = 2,  // any alignment: element loads
-    BIAS_F32_VEC = 3,
-    BIAS_F32_ANY = 4,
+    BIAS_BF16_VEC = 1,  // any element-aligned rows: 16-byte loads into registers, one block ahead
+    BIAS_F32_VEC = 3,   // fp32 bias, 16-byte loads at use
     BIAS_BF16_LDS = 5   // rows 16-byte aligned, N % 8 == 0: tile staged global -> LDS asynchronously
 };
 

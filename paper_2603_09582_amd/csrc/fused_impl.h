@@ -35,6 +35,12 @@
 
 namespace binattn {
 
+// 16-byte loads from addresses that are only element-aligned (gfx950 under HSA
+// supports unaligned vector loads; the compiler still emits one dwordx4 load).
+typedef u4v u4v_a2 __attribute__((aligned(2)));
+typedef float f4v __attribute__((ext_vector_type(4)));
+typedef f4v f4v_a4 __attribute__((aligned(4)));
+
 constexpr float LOG2E_F = 1.44269504088896340736f;
 constexpr float LOG2_255_F = 7.99435343685885793770f;
 
@@ -95,7 +101,7 @@ __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedPara
     const char *imgs = p.img + (int64_t)bh * p.nblk * L::BYTES;
 
     // ---- bias row of this lane ------------------------------------------------
-    const int bsb = (MODE == BIAS_F32_VEC || MODE == BIAS_F32_ANY) ? 4 : 2;  // bytes per element
+    const int bsb = (MODE == BIAS_F32_VEC) ? 4 : 2;  // bytes per element
     const char *brow = nullptr;
     if (MODE != BIAS_NONE)
         brow = static_cast<const char *>(p.bias) +
@@ -134,12 +140,12 @@ __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedPara
         const uint16_t *src = reinterpret_cast<const uint16_t *>(brow) + k0;
         if (blk * BV + BV <= N) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) braw[i] = *reinterpret_cast<const u4v *>(src + 8 * i);
+            for (int i = 0; i < 8; ++i) braw[i] = *reinterpret_cast<const u4v_a2 *>(src + 8 * i);
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 if (k0 + 8 * i + 8 <= N) {
-                    braw[i] = *reinterpret_cast<const u4v *>(src + 8 * i);
+                    braw[i] = *reinterpret_cast<const u4v_a2 *>(src + 8 * i);
                 } else {
                     unsigned e[8];
 #pragma unroll
@@ -178,29 +184,20 @@ __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedPara
                     bt[8 * i + 2 * j + 1] = bf16_hi(w[j]) * inv_alpha;
                 }
             }
-        } else if (MODE == BIAS_BF16_ANY) {
-            const uint16_t *src = reinterpret_cast<const uint16_t *>(brow) + k0;
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                bt[r] = (k0 + r < N) ? __uint_as_float((unsigned)src[r] << 16) * inv_alpha : 0.0f;
-        } else if (MODE == BIAS_F32_VEC) {
+        } else {  // BIAS_F32_VEC: 16-byte loads at float alignment, guarded at the row end
             const float *src = reinterpret_cast<const float *>(brow) + k0;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 if (k0 + 4 * i + 4 <= N) {
-                    const float4 w = *reinterpret_cast<const float4 *>(src + 4 * i);
-                    bt[4 * i] = w.x * inv_alpha; bt[4 * i + 1] = w.y * inv_alpha;
-                    bt[4 * i + 2] = w.z * inv_alpha; bt[4 * i + 3] = w.w * inv_alpha;
+                    const f4v w = *reinterpret_cast<const f4v_a4 *>(src + 4 * i);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) bt[4 * i + j] = w[j] * inv_alpha;
                 } else {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
                         bt[4 * i + j] = (k0 + 4 * i + j < N) ? src[4 * i + j] * inv_alpha : 0.0f;
                 }
             }
-        } else {
-            const float *src = reinterpret_cast<const float *>(brow) + k0;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) bt[r] = (k0 + r < N) ? src[r] * inv_alpha : 0.0f;
         }
         return bt;
     };
@@ -336,9 +333,14 @@ int launch_fused_dk(const FusedParams &p, int mode, hipStream_t stream) {
     const dim3 grid((unsigned)(((p.total_wg + 7) / 8) * 8)), block(FUSED_THREADS);
     switch (mode) {
 #define CASE(M) case M: hipLaunchKernelGGL((fused_kernel<DK, M>), grid, block, 0, stream, p); break;
-        CASE(BIAS_NONE) CASE(BIAS_BF16_VEC) CASE(BIAS_BF16_ANY) CASE(BIAS_F32_VEC) CASE(BIAS_F32_ANY)
-        CASE(BIAS_BF16_LDS)
+        CASE(BIAS_NONE) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC)
 #undef CASE
+        case BIAS_BF16_LDS:
+            if constexpr (DK <= 3) {
+                hipLaunchKernelGGL((fused_kernel<DK, BIAS_BF16_LDS>), grid, block, 0, stream, p);
+                break;
+            }
+            return BINATTN_ERR_SHAPE;
         default: return BINATTN_ERR_DTYPE;
     }
     return check_launch();

@@ -3,8 +3,7 @@
 // HBM-bound streaming kernel: every lane loads 16 contiguous bytes (8 bf16
 // channels of one token), turns them into 8 sign bits and one partial |x| sum.
 // The sign bytes of a tile of tokens are assembled in LDS and written out as
-// whole uint32 words, fully coalesced.  One float atomic per workgroup feeds
-// mu (pre-divided by N*d, so the buffer holds the mean when the grid drains).
+// whole uint32 words, fully coalesced.  Q and K go through one launch.
 #include "binattn_internal.h"
 
 namespace binattn {
@@ -35,49 +34,87 @@ __device__ __forceinline__ unsigned sign_bits8(uint4 w, float &asum) {
     return bits;
 }
 
-// C16 = d / 8 = 16-byte chunks per token.
+typedef unsigned u4p __attribute__((ext_vector_type(4)));
+
+struct PackSide {
+    const uint16_t *x;
+    Strides3 xs;
+    uint32_t *bits;
+    float *mu;
+};
+
+// One tile of PACK_TOKENS tokens of one head: sign bytes assembled in LDS, then
+// written as whole words.  Returns this thread's partial sum of |x|.
 template <int C16>
-__global__ __launch_bounds__(PACK_THREADS) void pack_kernel(const uint16_t *__restrict__ x,
-                                                            Strides3 xs, int H, int N,
-                                                            int ntile,
-                                                            uint32_t *__restrict__ bits,
-                                                            float *__restrict__ mu,
-                                                            float inv_count) {
-    constexpr int W = (C16 + 3) / 4;           // words per token
-    __shared__ uint32_t words[PACK_TOKENS * W];
-    __shared__ float wsum[PACK_THREADS / 64];
-
-    const int bh = blockIdx.x / ntile;
-    const int b = bh / H, h = bh % H;
-    const int n0 = (blockIdx.x % ntile) * PACK_TOKENS;
-    const int ntok = min(PACK_TOKENS, N - n0);
-    const uint16_t *xb = x + (int64_t)b * xs.b + (int64_t)h * xs.h;
-
+__device__ __forceinline__ float pack_tile(const uint16_t *__restrict__ xb, int64_t stride_n, int n0,
+                                           int ntok, uint32_t *__restrict__ ob, uint32_t *words) {
+    constexpr int W = (C16 + 3) / 4;  // words per token
     for (int i = threadIdx.x; i < PACK_TOKENS * W; i += PACK_THREADS) words[i] = 0u;
     __syncthreads();
-
     uint8_t *bytes = reinterpret_cast<uint8_t *>(words);
     float asum = 0.0f;
     for (int e = threadIdx.x; e < ntok * C16; e += PACK_THREADS) {
         const int tok = e / C16, c = e % C16;
-        const uint4 v = *reinterpret_cast<const uint4 *>(xb + (int64_t)(n0 + tok) * xs.n + 8 * c);
-        bytes[tok * (4 * W) + c] = (uint8_t)sign_bits8(v, asum);
+        const u4p v = *reinterpret_cast<const u4p *>(xb + (int64_t)(n0 + tok) * stride_n + 8 * c);
+        bytes[tok * (4 * W) + c] = (uint8_t)sign_bits8(make_uint4(v[0], v[1], v[2], v[3]), asum);
     }
     __syncthreads();
-
-    uint32_t *ob = bits + ((int64_t)bh * N + n0) * W;
     for (int i = threadIdx.x; i < ntok * W; i += PACK_THREADS) ob[i] = words[i];
+    return asum;
+}
 
-    // workgroup reduction of the |x| partial sums
+__device__ __forceinline__ float block_sum(float v, float *wsum) {
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) asum += __shfl_down(asum, off, 64);
-    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = asum;
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
     __syncthreads();
-    if (threadIdx.x == 0) {
-        float t = 0.0f;
-        for (int i = 0; i < PACK_THREADS / 64; ++i) t += wsum[i];
-        atomicAdd(mu + bh, t * inv_count);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float t = 0.0f;
+    for (int i = 0; i < PACK_THREADS / 64; ++i) t += wsum[i];
+    return t;
+}
+
+// Long sequences: one workgroup per (tensor, head, token tile); mu through one
+// float atomic per workgroup into a zeroed buffer.
+template <int C16>
+__global__ __launch_bounds__(PACK_THREADS) void pack_tile_kernel(PackSide q, PackSide k, int BH,
+                                                                 int H, int N, int ntile,
+                                                                 float inv_count) {
+    constexpr int W = (C16 + 3) / 4;
+    __shared__ uint32_t words[PACK_TOKENS * W];
+    __shared__ float wsum[PACK_THREADS / 64];
+    const int side = blockIdx.x / (BH * ntile);
+    const int rem = blockIdx.x % (BH * ntile);
+    const PackSide &S = side ? k : q;
+    const int bh = rem / ntile, n0 = (rem % ntile) * PACK_TOKENS;
+    const int b = bh / H, h = bh % H;
+    const uint16_t *xb = S.x + (int64_t)b * S.xs.b + (int64_t)h * S.xs.h;
+    const float a = pack_tile<C16>(xb, S.xs.n, n0, min(PACK_TOKENS, N - n0),
+                                   S.bits + ((int64_t)bh * N + n0) * W, words);
+    const float t = block_sum(a, wsum);
+    if (threadIdx.x == 0) atomicAdd(S.mu + bh, t * inv_count);
+}
+
+// Short sequences: one workgroup per (tensor, head) walks all token tiles and
+// stores mu itself: one launch, no atomics, no zero fill, deterministic.
+template <int C16>
+__global__ __launch_bounds__(PACK_THREADS) void pack_head_kernel(PackSide q, PackSide k, int BH,
+                                                                 int H, int N, float inv_count) {
+    constexpr int W = (C16 + 3) / 4;
+    __shared__ uint32_t words[PACK_TOKENS * W];
+    __shared__ float wsum[PACK_THREADS / 64];
+    const int side = blockIdx.x / BH, bh = blockIdx.x % BH;
+    const PackSide &S = side ? k : q;
+    const int b = bh / H, h = bh % H;
+    const uint16_t *xb = S.x + (int64_t)b * S.xs.b + (int64_t)h * S.xs.h;
+    float a = 0.0f;
+    for (int n0 = 0; n0 < N; n0 += PACK_TOKENS) {
+        a += pack_tile<C16>(xb, S.xs.n, n0, min(PACK_TOKENS, N - n0),
+                            S.bits + ((int64_t)bh * N + n0) * W, words);
+        __syncthreads();
     }
+    const float t = block_sum(a, wsum);
+    if (threadIdx.x == 0) S.mu[bh] = t * inv_count;
 }
 
 int launch_zero_f32(float *a, float *b, int n, hipStream_t stream) {
@@ -85,26 +122,37 @@ int launch_zero_f32(float *a, float *b, int n, hipStream_t stream) {
     return check_launch();
 }
 
+// Heads of at most this many tokens are packed by one workgroup each.
+constexpr int PACK_HEAD_MAX_TOKENS = 2048;
+
 template <int C16>
-static void launch_pack_t(const void *x, Strides3 xs, const Shape &s, uint32_t *bits, float *mu,
-                          hipStream_t stream) {
+static int launch_pack_t(const PackSide &q, const PackSide &k, const Shape &s, hipStream_t stream) {
+    const float inv = (float)(1.0 / ((double)s.N * (double)s.d));
+    if (s.N <= PACK_HEAD_MAX_TOKENS) {
+        hipLaunchKernelGGL(pack_head_kernel<C16>, dim3(2u * s.BH), dim3(PACK_THREADS), 0, stream, q, k,
+                           s.BH, s.H, s.N, inv);
+        return check_launch();
+    }
+    int rc = launch_zero_f32(q.mu, k.mu, s.BH, stream);
+    if (rc != BINATTN_OK) return rc;
     const int ntile = (s.N + PACK_TOKENS - 1) / PACK_TOKENS;
-    dim3 grid((unsigned)ntile * (unsigned)s.BH);
-    float inv = (float)(1.0 / ((double)s.N * (double)s.d));
-    hipLaunchKernelGGL(pack_kernel<C16>, grid, dim3(PACK_THREADS), 0, stream,
-                       static_cast<const uint16_t *>(x), xs, s.H, s.N, ntile, bits, mu, inv);
+    hipLaunchKernelGGL(pack_tile_kernel<C16>, dim3(2u * s.BH * ntile), dim3(PACK_THREADS), 0, stream,
+                       q, k, s.BH, s.H, s.N, ntile, inv);
+    return check_launch();
 }
 
-int launch_pack(const void *x, Strides3 xs, const Shape &s, uint32_t *bits, float *mu,
-                hipStream_t stream) {
+int launch_pack_qk(const void *q, Strides3 qs, const void *k, Strides3 ks, const Shape &s,
+                   uint32_t *q_bits, uint32_t *k_bits, float *mu_q, float *mu_k,
+                   hipStream_t stream) {
+    const PackSide Q = {static_cast<const uint16_t *>(q), qs, q_bits, mu_q};
+    const PackSide K = {static_cast<const uint16_t *>(k), ks, k_bits, mu_k};
     switch (s.d / 8) {
-#define CASE(c) case c: launch_pack_t<c>(x, xs, s, bits, mu, stream); break;
+#define CASE(c) case c: return launch_pack_t<c>(Q, K, s, stream);
         CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8)
         CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14) CASE(15) CASE(16)
 #undef CASE
         default: return BINATTN_ERR_SHAPE;
     }
-    return check_launch();
 }
 
 }  // namespace binattn

@@ -34,15 +34,11 @@ __device__ __forceinline__ int key_of_position(int pos) {
     return 64 * g + 16 * t + r;
 }
 
+// Key block `blk` of one head: sign words -> FP4 rows of the block image.
 // One thread per (row position, sign word): 32 channels -> 16 bytes of FP4 codes.
-__global__ __launch_bounds__(PREP_THREADS) void expand_k_kernel(const uint32_t *__restrict__ k_bits,
-                                                                int N, int d, int W, int nblk,
-                                                                int img_bytes, int KP,
-                                                                char *__restrict__ img) {
-    const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
+__device__ __forceinline__ void expand_k_block(const uint32_t *__restrict__ kb, int N, int d, int W,
+                                               int blk, int KP, char *__restrict__ dst) {
     const int W2 = 2 * ((W + 1) / 2);  // words per row incl. the zero word that pads to 64 channels
-    const uint32_t *kb = k_bits + (int64_t)bh * N * W;
-    char *dst = img + ((int64_t)bh * nblk + blk) * img_bytes;
     for (int i = threadIdx.x; i < BV * W2; i += PREP_THREADS) {
         const int pos = i / W2, w = i % W2;
         const int key = blk * BV + key_of_position(pos);
@@ -50,36 +46,38 @@ __global__ __launch_bounds__(PREP_THREADS) void expand_k_kernel(const uint32_t *
         const uint32_t word = live ? kb[(int64_t)key * W + w] : 0u;
         const int valid = live ? d - 32 * w : 0;  // real channels in this word
         u4 o;
-        unsigned *op = reinterpret_cast<unsigned *>(&o);
 #pragma unroll
         for (int n = 0; n < 4; ++n)
-            op[n] = (8 * n < valid) ? fp4_pm1_bits8((word >> (8 * n)) & 0xFFu) : 0u;
+            o[n] = (8 * n < valid) ? fp4_pm1_bits8((word >> (8 * n)) & 0xFFu) : 0u;
         *reinterpret_cast<u4 *>(dst + (int64_t)pos * KP + 16 * w) = o;
     }
 }
 
-__device__ __forceinline__ void unpack8(uint4 w, float f[8]) {
-    const unsigned dw[4] = {w.x, w.y, w.z, w.w};
+__global__ __launch_bounds__(PREP_THREADS) void expand_k_kernel(const uint32_t *__restrict__ k_bits,
+                                                                int N, int d, int W, int nblk,
+                                                                int img_bytes, int KP,
+                                                                char *__restrict__ img) {
+    const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
+    expand_k_block(k_bits + (int64_t)bh * N * W, N, d, W, blk, KP,
+                   img + ((int64_t)bh * nblk + blk) * img_bytes);
+}
+
+__device__ __forceinline__ void unpack8(u4 w, float f[8]) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        f[2 * i] = __uint_as_float(dw[i] << 16);
-        f[2 * i + 1] = __uint_as_float(dw[i] & 0xffff0000u);
+        f[2 * i] = __uint_as_float(w[i] << 16);
+        f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
     }
 }
 
-// Partial absmax over VCHUNK token rows: amax[bh][chunk][c].
+// absmax over token rows [n0, n1) of one head, all threads of the workgroup:
+// on return thread c < 8 * C16 holds max_n |v[n][c]| (other threads 0).
+// smax: LDS scratch of (PREP_THREADS / C16) * 8 * C16 floats.
 template <int C16>
-__global__ __launch_bounds__(PREP_THREADS) void v_absmax_kernel(const uint16_t *__restrict__ v,
-                                                                Strides3 vs, int H, int N, int DKP,
-                                                                int nchunk,
-                                                                float *__restrict__ amax) {
+__device__ __forceinline__ float absmax_rows(const uint16_t *__restrict__ vb, int64_t stride_n,
+                                             int n0, int n1, float *smax) {
     constexpr int RT = PREP_THREADS / C16;  // token rows per pass
     constexpr int D = 8 * C16;
-    __shared__ float smax[RT * D];
-    const int chunk = blockIdx.x % nchunk, bh = blockIdx.x / nchunk;
-    const int b = bh / H, h = bh % H;
-    const uint16_t *vb = v + (int64_t)b * vs.b + (int64_t)h * vs.h;
-    const int n0 = chunk * VCHUNK, n1 = min(N, n0 + VCHUNK);
     const int c = threadIdx.x % C16, r0 = threadIdx.x / C16;
     if (r0 < RT) {
         float m[8];
@@ -87,7 +85,7 @@ __global__ __launch_bounds__(PREP_THREADS) void v_absmax_kernel(const uint16_t *
         for (int i = 0; i < 8; ++i) m[i] = 0.0f;
         for (int n = n0 + r0; n < n1; n += RT) {
             float f[8];
-            unpack8(*reinterpret_cast<const uint4 *>(vb + (int64_t)n * vs.n + 8 * c), f);
+            unpack8(*reinterpret_cast<const u4 *>(vb + (int64_t)n * stride_n + 8 * c), f);
 #pragma unroll
             for (int i = 0; i < 8; ++i) m[i] = fmaxf(m[i], fabsf(f[i]));
         }
@@ -95,39 +93,26 @@ __global__ __launch_bounds__(PREP_THREADS) void v_absmax_kernel(const uint16_t *
         for (int i = 0; i < 8; ++i) smax[r0 * D + 8 * c + i] = m[i];
     }
     __syncthreads();
-    if (threadIdx.x < D) {
-        float a = 0.0f;
+    float a = 0.0f;
+    if (threadIdx.x < D)
         for (int r = 0; r < RT; ++r) a = fmaxf(a, smax[r * D + threadIdx.x]);
-        amax[((int64_t)bh * nchunk + chunk) * DKP + threadIdx.x] = a;
-    }
+    return a;
 }
 
-// One key block of one head: delta_v, codes (channel-major) and 128 * column sums.
-template <int C16>
-__global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(const uint16_t *__restrict__ v,
-                                                               Strides3 vs, int H, int N, int DKP,
-                                                               int nchunk, int nblk,
-                                                               const float *__restrict__ amax,
-                                                               float *__restrict__ delta,
-                                                               int img_bytes, int v_off, int cs_off,
-                                                               char *__restrict__ img) {
-    constexpr int D = 8 * C16;
-    constexpr int LDT = BV + 16;  // LDS row pitch in bytes
-    __shared__ float sdelta[D];
-    __shared__ __attribute__((aligned(16))) int8_t tile[128 * LDT];  // up to DKP = 128 rows
-    const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
-    const int b = bh / H, h = bh % H;
-    const uint16_t *vb = v + (int64_t)b * vs.b + (int64_t)h * vs.h;
+// Eq. 7 scale: absmax / 127 (IEEE fp32 division); 1 for an all-zero channel.
+__device__ __forceinline__ float delta_of_absmax(float a) {
+    return (a == 0.0f) ? 1.0f : __fdiv_rn(a, 127.0f);
+}
 
-    if (threadIdx.x < D) {
-        float a = 0.0f;
-        for (int i = 0; i < nchunk; ++i)
-            a = fmaxf(a, amax[((int64_t)bh * nchunk + i) * DKP + threadIdx.x]);
-        // Eq. 7 scale: absmax / 127 (IEEE fp32 division); 1 for an all-zero channel.
-        const float dl = (a == 0.0f) ? 1.0f : __fdiv_rn(a, 127.0f);
-        sdelta[threadIdx.x] = dl;
-        if (blk == 0) delta[(int64_t)bh * DKP + threadIdx.x] = dl;
-    }
+// Key block `blk` of one head: codes (channel-major) and the accumulator seeds
+// into the block image.  sdelta (LDS) holds the head's per-channel scales;
+// tile is LDS scratch of 128 * (BV + 16) bytes.
+template <int C16>
+__device__ __forceinline__ void quant_v_block(const uint16_t *__restrict__ vb, int64_t stride_n,
+                                              int N, int DKP, int blk, const float *sdelta,
+                                              int8_t *tile, int v_off, int cs_off,
+                                              char *__restrict__ dst) {
+    constexpr int LDT = BV + 16;  // LDS row pitch in bytes = Image::VP
     for (int i = threadIdx.x; i < DKP * LDT / 4; i += PREP_THREADS)
         reinterpret_cast<uint32_t *>(tile)[i] = 0u;
     __syncthreads();
@@ -137,7 +122,7 @@ __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(const uint16_t *_
     for (int e = threadIdx.x; e < nrow * C16; e += PREP_THREADS) {
         const int jl = e / C16, c = e % C16;
         float f[8];
-        unpack8(*reinterpret_cast<const uint4 *>(vb + (int64_t)(j0 + jl) * vs.n + 8 * c), f);
+        unpack8(*reinterpret_cast<const u4 *>(vb + (int64_t)(j0 + jl) * stride_n + 8 * c), f);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             // Eq. 7: code = round-to-nearest-even(v / delta), clamped to [-127, 127]
@@ -148,7 +133,6 @@ __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(const uint16_t *_
     }
     __syncthreads();
 
-    char *dst = img + ((int64_t)bh * nblk + blk) * img_bytes;
     for (int i = threadIdx.x; i < DKP * (BV / 16); i += PREP_THREADS) {
         const int c = i / (BV / 16), part = i % (BV / 16);
         const u4 val = *reinterpret_cast<const u4 *>(tile + c * LDT + 16 * part);
@@ -159,6 +143,73 @@ __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(const uint16_t *_
         for (int j = 0; j < BV; ++j) sum += (int)tile[threadIdx.x * LDT + j];
         reinterpret_cast<int *>(dst + cs_off)[threadIdx.x] = PV_MAGIC_BITS + 128 * sum;
     }
+}
+
+// Long sequences, step 1: partial absmax over VCHUNK token rows, amax[bh][chunk][c].
+template <int C16>
+__global__ __launch_bounds__(PREP_THREADS) void v_absmax_kernel(const uint16_t *__restrict__ v,
+                                                                Strides3 vs, int H, int N, int DKP,
+                                                                int nchunk,
+                                                                float *__restrict__ amax) {
+    __shared__ float smax[(PREP_THREADS / C16) * 8 * C16];
+    const int chunk = blockIdx.x % nchunk, bh = blockIdx.x / nchunk;
+    const int b = bh / H, h = bh % H;
+    const uint16_t *vb = v + (int64_t)b * vs.b + (int64_t)h * vs.h;
+    const float a = absmax_rows<C16>(vb, vs.n, chunk * VCHUNK, min(N, chunk * VCHUNK + VCHUNK), smax);
+    if (threadIdx.x < 8 * C16) amax[((int64_t)bh * nchunk + chunk) * DKP + threadIdx.x] = a;
+}
+
+// Long sequences, step 2: one key block of one head.
+template <int C16>
+__global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(const uint16_t *__restrict__ v,
+                                                               Strides3 vs, int H, int N, int DKP,
+                                                               int nchunk, int nblk,
+                                                               const float *__restrict__ amax,
+                                                               float *__restrict__ delta,
+                                                               int img_bytes, int v_off, int cs_off,
+                                                               char *__restrict__ img) {
+    __shared__ float sdelta[8 * C16];
+    __shared__ __attribute__((aligned(16))) int8_t tile[128 * (BV + 16)];
+    const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
+    const int b = bh / H, h = bh % H;
+    const uint16_t *vb = v + (int64_t)b * vs.b + (int64_t)h * vs.h;
+    if (threadIdx.x < 8 * C16) {
+        float a = 0.0f;
+        for (int i = 0; i < nchunk; ++i)
+            a = fmaxf(a, amax[((int64_t)bh * nchunk + i) * DKP + threadIdx.x]);
+        const float dl = delta_of_absmax(a);
+        sdelta[threadIdx.x] = dl;
+        if (blk == 0) delta[(int64_t)bh * DKP + threadIdx.x] = dl;
+    }
+    quant_v_block<C16>(vb, vs.n, N, DKP, blk, sdelta, tile, v_off, cs_off,
+                       img + ((int64_t)bh * nblk + blk) * img_bytes);
+}
+
+// Short sequences: everything for one key block of one head in ONE launch.  Every
+// workgroup recomputes the head's absmax itself (N * d elements, cheap while N is
+// small and served by L2 after the first reader), so there is no dependency
+// between workgroups and no second or third launch.
+template <int C16>
+__global__ __launch_bounds__(PREP_THREADS) void prep_block_kernel(
+    const uint16_t *__restrict__ v, Strides3 vs, const uint32_t *__restrict__ k_bits, int H, int N,
+    int d, int DKP, int nblk, float *__restrict__ delta, int img_bytes, int KP, int v_off, int cs_off,
+    char *__restrict__ img) {
+    __shared__ float smax[(PREP_THREADS / C16) * 8 * C16];
+    __shared__ float sdelta[8 * C16];
+    __shared__ __attribute__((aligned(16))) int8_t tile[128 * (BV + 16)];
+    const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
+    const int b = bh / H, h = bh % H;
+    const int W = (d + 31) / 32;
+    const uint16_t *vb = v + (int64_t)b * vs.b + (int64_t)h * vs.h;
+    char *dst = img + ((int64_t)bh * nblk + blk) * img_bytes;
+    expand_k_block(k_bits + (int64_t)bh * N * W, N, d, W, blk, KP, dst);
+    const float a = absmax_rows<C16>(vb, vs.n, 0, N, smax);
+    if (threadIdx.x < 8 * C16) {
+        const float dl = delta_of_absmax(a);
+        sdelta[threadIdx.x] = dl;
+        if (blk == 0) delta[(int64_t)bh * DKP + threadIdx.x] = dl;
+    }
+    quant_v_block<C16>(vb, vs.n, N, DKP, blk, sdelta, tile, v_off, cs_off, dst);
 }
 
 // Codes and delta from the private layout into [B,H,N,d] / [B,H,d].
@@ -192,25 +243,38 @@ int launch_expand_k(const uint32_t *k_bits, const Shape &s, char *ws, const Work
     return check_launch();
 }
 
+// Sequences up to this many key blocks take the single-launch path.
+constexpr int PREP_FUSED_MAX_BLOCKS = 16;
+
 template <int C16>
-static void launch_quant_v_t(const void *v, Strides3 vs, const Shape &s, char *ws,
-                             const Workspace &w, hipStream_t stream) {
+static void launch_quant_v_t(const void *v, Strides3 vs, const uint32_t *k_bits, const Shape &s,
+                             char *ws, const Workspace &w, hipStream_t stream) {
     const uint16_t *vp = static_cast<const uint16_t *>(v);
     float *amax = reinterpret_cast<float *>(ws + w.amax);
     float *delta = reinterpret_cast<float *>(ws + w.delta);
     int KP, v_off, cs_off;
     image_offsets(s.DK, &KP, &v_off, &cs_off);
+    if (k_bits != nullptr && s.nblk <= PREP_FUSED_MAX_BLOCKS) {
+        hipLaunchKernelGGL(prep_block_kernel<C16>, dim3((unsigned)s.nblk * s.BH), dim3(PREP_THREADS),
+                           0, stream, vp, vs, k_bits, s.H, s.N, s.d, s.DKP, s.nblk, delta,
+                           w.img_bytes, KP, v_off, cs_off, ws + w.img);
+        return;
+    }
     hipLaunchKernelGGL(v_absmax_kernel<C16>, dim3((unsigned)s.nchunk * s.BH), dim3(PREP_THREADS),
                        0, stream, vp, vs, s.H, s.N, s.DKP, s.nchunk, amax);
     hipLaunchKernelGGL(v_quant_kernel<C16>, dim3((unsigned)s.nblk * s.BH), dim3(PREP_THREADS), 0,
                        stream, vp, vs, s.H, s.N, s.DKP, s.nchunk, s.nblk, amax, delta, w.img_bytes,
                        v_off, cs_off, ws + w.img);
+    if (k_bits != nullptr)
+        hipLaunchKernelGGL(expand_k_kernel, dim3((unsigned)s.nblk * s.BH), dim3(PREP_THREADS), 0,
+                           stream, k_bits, s.N, s.d, s.W, s.nblk, w.img_bytes, KP, ws + w.img);
 }
 
-int launch_quant_v(const void *v, Strides3 vs, const Shape &s, char *ws, const Workspace &w,
-                   hipStream_t stream) {
+// V quantisation and (if k_bits is not null) the key operand into the block images.
+int launch_prepare(const void *v, Strides3 vs, const uint32_t *k_bits, const Shape &s, char *ws,
+                   const Workspace &w, hipStream_t stream) {
     switch (s.d / 8) {
-#define CASE(c) case c: launch_quant_v_t<c>(v, vs, s, ws, w, stream); break;
+#define CASE(c) case c: launch_quant_v_t<c>(v, vs, k_bits, s, ws, w, stream); break;
         CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8)
         CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14) CASE(15) CASE(16)
 #undef CASE
