@@ -147,7 +147,10 @@ int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
     p.B = B; p.H = H; p.N = N; p.d = d;
     p.nblk = s.nblk;
     p.nrb = (N + BR - 1) / BR;
-    p.total_wg = p.nrb * s.BH;
+    // Long sequences with a batch-shared, LDS-staged bias: pair batch entries in one
+    // workgroup so that the bias stream is fetched once per pair.
+    p.nb = (mode == BIAS_BF16_LDS && bs.b == 0 && B % 2 == 0 && s.DK <= 2 && s.nblk >= 8) ? 2 : 1;
+    p.total_wg = p.nrb * H * (B / p.nb);
     switch (s.DK) {
         case 1: return launch_fused_dk<1>(p, mode, st);
         case 2: return launch_fused_dk<2>(p, mode, st);

@@ -62,39 +62,78 @@ __device__ __forceinline__ void load_q_operand(const uint32_t *__restrict__ q_wo
     }
 }
 
-// QK tile t of the block image at `img`: for this lane's query, register r is
-// cin[r] + (s_i . t_j) with key j = block start + 64 g + 16 t + r.
+// A operand rows of QK tile t for this lane (LDS reads only).
 template <int DK>
-__device__ __forceinline__ v16f qk_tile(const char *img, int t, int m, int g,
-                                        const v4i qB[(DK + 1) / 2], v16f cin) {
+__device__ __forceinline__ void load_k_operand(const char *img, int t, int m, int g,
+                                               v4i ka[(DK + 1) / 2]) {
     using L = Image<DK>;
 #pragma unroll
-    for (int s = 0; s < L::DK2; ++s) {
-        const v4i a = *reinterpret_cast<const v4i *>(img + L::K_OFF + (32 * t + m) * L::KP + 32 * s + 16 * g);
-        const v8i a8 = {a[0], a[1], a[2], a[3], 0, 0, 0, 0};
+    for (int s = 0; s < L::DK2; ++s)
+        ka[s] = *reinterpret_cast<const v4i *>(img + L::K_OFF + (32 * t + m) * L::KP + 32 * s + 16 * g);
+}
+
+// QK tile: for this lane's query, register r of the result is
+// cin[r] + (s_i . t_j) with key j = block start + 64 g + 16 t + r.
+template <int DK2>
+__device__ __forceinline__ v16f qk_mfma(const v4i ka[DK2], const v4i qB[DK2], v16f cin) {
+#pragma unroll
+    for (int s = 0; s < DK2; ++s) {
+        const v8i a8 = {ka[s][0], ka[s][1], ka[s][2], ka[s][3], 0, 0, 0, 0};
         const v8i b8 = {qB[s][0], qB[s][1], qB[s][2], qB[s][3], 0, 0, 0, 0};
         cin = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, cin, 4, 4, 0, 0, 0, 0);
     }
     return cin;
 }
 
-// Asynchronous copy of one block image (L::BYTES, a multiple of 1 KiB) from
-// global memory straight into LDS: each wave moves 1 KiB per instruction
-// (64 lanes x 16 bytes, LDS address = base + 16 * lane).
 template <int DK>
-__device__ __forceinline__ void dma_image(const char *__restrict__ gsrc, char *ldst, int wave, int lane) {
+__device__ __forceinline__ v16f qk_tile(const char *img, int t, int m, int g,
+                                        const v4i qB[(DK + 1) / 2], v16f cin) {
+    v4i ka[(DK + 1) / 2];
+    load_k_operand<DK>(img, t, m, g, ka);
+    return qk_mfma<(DK + 1) / 2>(ka, qB, cin);
+}
+
+// LDS byte offset of a pointer into a __shared__ array.
+__device__ __forceinline__ unsigned lds_offset(const void *p) {
+    return (unsigned)(size_t)(__attribute__((address_space(3))) const char *)p;
+}
+
+// One asynchronous 16-byte-per-lane copy global -> LDS: lane L's 16 bytes land at
+// lds_base + 16 L (lds_base wave-uniform).  Issued through inline assembly so that
+// the compiler does not serialise later LDS reads of OTHER buffers against it; the
+// callers order it by hand (wait_vmem + barrier before the data is read).
+__device__ __forceinline__ void dma16(const void *gptr, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_base), "v"(gptr)
+                 : "memory", "m0");
+}
+
+// Asynchronous copy of one block image (L::BYTES, a multiple of 1 KiB) from
+// global memory straight into LDS: each of the four waves of a batch entry moves
+// 1 KiB per instruction.
+template <int DK>
+__device__ __forceinline__ void dma_image(const char *__restrict__ gsrc, unsigned ldst, int wave, int lane) {
     using L = Image<DK>;
     constexpr int NCH = L::BYTES / 1024;
 #pragma unroll
     for (int i = 0; i < (NCH + 3) / 4; ++i) {
         const int c = wave + 4 * i;
-        if (c < NCH)
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(gsrc + c * 1024 + lane * 16),
-                (__attribute__((address_space(3))) void *)(ldst + c * 1024), 16, 0, 0);
+        if (c < NCH) dma16(gsrc + c * 1024 + lane * 16, ldst + c * 1024);
     }
 }
 
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+// max / sum over the two lanes L and L ^ 32 (they share a query row), on the vector ALU.
+__device__ __forceinline__ float pair_max(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float pair_sum(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 
 }  // namespace binattn

@@ -138,6 +138,7 @@ struct FusedParams {
     const char *img;     // block images
     const float *delta;
     int B, H, N, d, nblk, nrb, total_wg;
+    int nb;              // batch entries per workgroup (1 or 2)
 };
 
 // Defined (and explicitly instantiated) in fused_dk<DK>.hip, DK = ceil(d / 32).

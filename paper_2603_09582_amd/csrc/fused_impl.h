@@ -53,17 +53,28 @@ __device__ __forceinline__ unsigned f32_to_bf16_rne(float f) {
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
-template <int DK, int MODE>
-__global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedParams p) {
+// NB = batch entries per workgroup.  NB = 2 (only with BIAS_BF16_LDS and a bias shared
+// over the batch) puts two batch entries of the same (head, row block) into one
+// 8-wave workgroup: waves 0-3 work on entry 2 bp, waves 4-7 on entry 2 bp + 1, and
+// both read the SAME bias tile from LDS, so the bias - the dominant HBM stream of
+// long sequences - is fetched once per pair and can be double-buffered.
+template <int DK, int MODE, int NB>
+__global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const FusedParams p) {
     using L = Image<DK>;
     constexpr int DKP = 32 * DK;
     constexpr int DK2 = L::DK2;
-    // Two separate arrays (not one [2][..]) so that the compiler can tell the
-    // buffer being filled from the buffer being read.
-    __shared__ __attribute__((aligned(1024))) char bufA[L::BYTES];
-    __shared__ __attribute__((aligned(1024))) char bufB[L::BYTES];
-    // BIAS_BF16_LDS: wave-private staging of the wave's 32 x 128 bias tile (8 KiB per wave)
-    __shared__ __attribute__((aligned(1024))) char biasbuf[MODE == BIAS_BF16_LDS ? 4 * 8192 : 1024];
+    constexpr bool LDS_BIAS = MODE == BIAS_BF16_LDS;
+    constexpr bool BIAS_DB = LDS_BIAS && NB == 2;  // bias tiles double-buffered and shared
+    // V operand rows of this many channel blocks are fetched from LDS before the
+    // exponential phase (the rest just before their MFMAs): hides the LDS latency
+    // where the register budget allows it.
+    constexpr int PRE = DK <= 2 ? DK : 1;
+    __shared__ __attribute__((aligned(1024))) char bufA[NB * L::BYTES];
+    __shared__ __attribute__((aligned(1024))) char bufB[NB * L::BYTES];
+    // BIAS_BF16_LDS: staging of the 32 x 128 bias tiles, 8 KiB per 32-row group.
+    // NB = 1: one region per wave, private to it.  NB = 2: two buffers shared by the pair.
+    __shared__ __attribute__((aligned(1024))) char biasA[LDS_BIAS ? 4 * 8192 : 1024];
+    __shared__ __attribute__((aligned(1024))) char biasB[BIAS_DB ? 4 * 8192 : 1024];
 
     // Workgroup -> work item.  Consecutive workgroup ids go to different XCDs, so
     // the id is first turned into (xcd, slot) and work items that share a bias
@@ -72,13 +83,15 @@ __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedPara
     const int per_xcd = (p.total_wg + 7) >> 3;
     const int u = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (u >= p.total_wg) return;
-    const int b = u % p.B;
-    const int rb = (u / p.B) % p.nrb;
-    const int h = u / (p.B * p.nrb);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) & 3);  // 32-row group
+    const int bsel = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);        // batch entry in the workgroup
+    const int nbp = p.B / NB;
+    const int b = (u % nbp) * NB + bsel;
+    const int rb = (u / nbp) % p.nrb;
+    const int h = u / (nbp * p.nrb);
     const int bh = b * p.H + h;
     const int N = p.N, d = p.d;
-
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 31, g = lane >> 5;
     const int q = rb * BR + wave * ROWS_PER_WAVE + m;  // this lane's query row
     const int qc = min(q, N - 1);                      // clamped for loads
@@ -100,10 +113,10 @@ __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedPara
 
     const char *imgs = p.img + (int64_t)bh * p.nblk * L::BYTES;
 
-    // ---- bias row of this lane ------------------------------------------------
+    // ---- bias access ----------------------------------------------------------
     const int bsb = (MODE == BIAS_F32_VEC) ? 4 : 2;  // bytes per element
-    const char *brow = nullptr;
-    if (MODE != BIAS_NONE)
+    const char *brow = nullptr;                      // this lane's bias row (register modes)
+    if (MODE == BIAS_BF16_VEC || MODE == BIAS_F32_VEC)
         brow = static_cast<const char *>(p.bias) +
                ((int64_t)b * p.bs.b + (int64_t)h * p.bs.h + (int64_t)qc * p.bs.n) * bsb;
     // BIAS_BF16_LDS: the tile is fetched with full-cache-line requests (8 lanes cover the
@@ -111,31 +124,32 @@ __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedPara
     // 8 rg + [0, 8) x keys 64 gh + [0, 64); lane 8 r + s fetches 16-byte chunk (s ^ r) of row
     // r, so that chunk c of row r lands at 128 r + 16 (c ^ r): the later 16-byte reads of 8
     // consecutive rows at one chunk index hit 8 different bank groups.
-    char *myb = biasbuf + (MODE == BIAS_BF16_LDS ? wave * 8192 : 0);
-    const char *bsrc[4] = {nullptr, nullptr, nullptr, nullptr};
-    const int dma_r = lane >> 3, dma_c = (lane & 7) ^ (lane >> 3);
-    if (MODE == BIAS_BF16_LDS) {
+    // A wave copies RGW of the four 8-row groups of its 32-row tile: all four when the
+    // tile is its own (NB = 1), two when the tile is shared with the other batch entry.
+    constexpr int RGW = 4 / NB;
+    const char *bsrc[RGW];
+    const int dma_c = (lane & 7) ^ (lane >> 3);
 #pragma unroll
-        for (int rg = 0; rg < 4; ++rg) {
-            const int row = min(rb * BR + wave * ROWS_PER_WAVE + 8 * rg + dma_r, N - 1);
-            bsrc[rg] = static_cast<const char *>(p.bias) +
-                       ((int64_t)b * p.bs.b + (int64_t)h * p.bs.h + (int64_t)row * p.bs.n) * 2 + 16 * dma_c;
+    for (int j = 0; j < RGW; ++j) {
+        bsrc[j] = nullptr;
+        if (LDS_BIAS) {
+            const int row = min(rb * BR + wave * ROWS_PER_WAVE + 8 * (RGW * bsel + j) + (lane >> 3), N - 1);
+            bsrc[j] = static_cast<const char *>(p.bias) +
+                      ((int64_t)b * p.bs.b + (int64_t)h * p.bs.h + (int64_t)row * p.bs.n) * 2 + 16 * dma_c;
         }
     }
-    auto dma_bias = [&](int blk) {
+    auto dma_bias = [&](int blk, unsigned region) {  // region: LDS offset of this wave's 8 KiB tile
 #pragma unroll
-        for (int rg = 0; rg < 4; ++rg)
+        for (int j = 0; j < RGW; ++j)
 #pragma unroll
             for (int gh = 0; gh < 2; ++gh) {
                 const int key0 = blk * BV + 64 * gh + 8 * dma_c;
                 if (key0 + 8 <= N)
-                    __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void *)(bsrc[rg] + (blk * BV + 64 * gh) * 2),
-                        (__attribute__((address_space(3))) void *)(myb + (rg * 2 + gh) * 1024), 16, 0, 0);
+                    dma16(bsrc[j] + (blk * BV + 64 * gh) * 2, region + ((RGW * bsel + j) * 2 + gh) * 1024);
             }
     };
-    u4v braw[8];  // BIAS_BF16_VEC: the 64 bias values of the block, prefetched
-    auto load_bias_vec = [&](int blk) {
+    u4v braw[8];  // the 64 bf16 bias values of this lane for the current block
+    auto load_bias_vec = [&](int blk) {  // BIAS_BF16_VEC: registers straight from global memory
         const int k0 = blk * BV + 64 * g;
         const uint16_t *src = reinterpret_cast<const uint16_t *>(brow) + k0;
         if (blk * BV + BV <= N) {
@@ -163,21 +177,10 @@ __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedPara
         if (MODE == BIAS_NONE) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) bt[r] = 0.0f;
-        } else if (MODE == BIAS_BF16_VEC) {
+        } else if (MODE == BIAS_BF16_VEC || MODE == BIAS_BF16_LDS) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const u4v w = braw[2 * t + i];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    bt[8 * i + 2 * j] = bf16_lo(w[j]) * inv_alpha;
-                    bt[8 * i + 2 * j + 1] = bf16_hi(w[j]) * inv_alpha;
-                }
-            }
-        } else if (MODE == BIAS_BF16_LDS) {
-            const char *row = myb + ((m >> 3) * 2 + g) * 1024 + 128 * (m & 7);
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const u4v w = *reinterpret_cast<const u4v *>(row + 16 * ((2 * t + i) ^ (m & 7)));
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     bt[8 * i + 2 * j] = bf16_lo(w[j]) * inv_alpha;
@@ -211,24 +214,50 @@ __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedPara
 #pragma unroll
         for (int r = 0; r < 16; ++r) Of[cb][r] = 0.0f;
 
-    // One key/value block: compute on `cur`, prefetch block it + 1 into `nxt`.
-    auto step = [&](int it, const char *cur, char *nxt) {
+    // One key/value block: compute on the image at `cur`, prefetch block it + 1 into the
+    // image buffer at LDS offset `nxt`.  bcur / bnxt: this wave's bias tile region now and
+    // for the next block (the same region unless the bias is double-buffered).
+    auto step = [&](int it, const char *cur, unsigned nxt, const char *bcur, unsigned bnxt) {
         const bool more = it + 1 < p.nblk;
+        // 0. start the copies of the next block
         if (more) dma_image<DK>(imgs + (int64_t)(it + 1) * L::BYTES, nxt, wave, lane);
+        if (BIAS_DB && more) dma_bias(it + 1, bnxt);
 
-        // 1. T = I + b / alpha
+        // 1. all LDS reads of the logit phase go out together: bias tile, key rows
+        if (LDS_BIAS) {
+            const char *row = bcur + ((m >> 3) * 2 + g) * 1024 + 128 * (m & 7);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) braw[i] = *reinterpret_cast<const u4v *>(row + 16 * (i ^ (m & 7)));
+        }
+        v4i ka[KT][DK2];
+#pragma unroll
+        for (int t = 0; t < KT; ++t) load_k_operand<DK>(cur, t, m, g, ka[t]);
+        //    T = I + b / alpha
         v16f T[KT];
 #pragma unroll
-        for (int t = 0; t < KT; ++t) T[t] = qk_tile<DK>(cur, t, m, g, qB, bias_tile(it, t));
-        if (MODE == BIAS_BF16_VEC && more) {
-            __builtin_amdgcn_sched_barrier(0);  // keep the prefetch behind the last use of braw
-            load_bias_vec(it + 1);
+        for (int t = 0; t < KT; ++t) T[t] = qk_mfma<DK2>(ka[t], qB, bias_tile(it, t));
+        __builtin_amdgcn_sched_barrier(0);
+        if (MODE == BIAS_BF16_VEC && more) load_bias_vec(it + 1);  // braw is free again
+        if (LDS_BIAS && !BIAS_DB && more) {
+            wait_lds();              // this block's tile has been read into registers
+            dma_bias(it + 1, bnxt);  // refill the wave's own region
         }
-        if (MODE == BIAS_BF16_LDS && more) {
-            __builtin_amdgcn_sched_barrier(0);
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this block's tile has been read
-            dma_bias(it + 1);                                   // refill the wave's region
+        //    the LDS reads of the P.V phase go out now and land during the exponentials
+        v16i acc[DK];
+        v4i va[PRE][KT];
+#pragma unroll
+        for (int cb = 0; cb < PRE; ++cb) {
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const v4i c4 = *reinterpret_cast<const v4i *>(cur + L::CS_OFF + 4 * (32 * cb + 8 * q4 + 4 * g));
+                acc[cb][4 * q4] = c4[0]; acc[cb][4 * q4 + 1] = c4[1];
+                acc[cb][4 * q4 + 2] = c4[2]; acc[cb][4 * q4 + 3] = c4[3];
+            }
+#pragma unroll
+            for (int t = 0; t < KT; ++t)
+                va[cb][t] = *reinterpret_cast<const v4i *>(cur + L::V_OFF + (32 * cb + m) * L::VP + 64 * g + 16 * t);
         }
+
         if (it * BV + BV > N) {  // ragged last block: keys beyond N never count
 #pragma unroll
             for (int t = 0; t < KT; ++t)
@@ -243,8 +272,7 @@ __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedPara
         for (int t = 0; t < KT; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, T[t][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
+        const float m_new = fmaxf(m_run, pair_max(mx));
         const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;  // whole row masked so far
         const float resc = __builtin_amdgcn_exp2f((m_run - m_use) * a2);  // e^{m_old - m_new}
         const float cexp = LOG2_255_F - m_use * a2;
@@ -270,42 +298,54 @@ __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedPara
         l_run = fmaf(l_run, resc, ls0 + ls1);
         rho = fmaf(rho, resc, 1.0f);
 
-        // 4-5. O = e^{m_old - m_new} O + P~ . V~
+        // 4. P~ . V~ : the prefetched channel blocks as interleaved MFMA chains ...
 #pragma unroll
-        for (int cb = 0; cb < DK; ++cb) {
-            v16i acc;
+        for (int t = 0; t < KT; ++t)
+#pragma unroll
+            for (int cb = 0; cb < PRE; ++cb)
+                acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(va[cb][t], pk[t], acc[cb], 0, 0, 0);
+        //    ... then the remaining ones
+#pragma unroll
+        for (int cb = PRE; cb < DK; ++cb) {
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
                 const v4i c4 = *reinterpret_cast<const v4i *>(cur + L::CS_OFF + 4 * (32 * cb + 8 * q4 + 4 * g));
-                acc[4 * q4] = c4[0]; acc[4 * q4 + 1] = c4[1]; acc[4 * q4 + 2] = c4[2]; acc[4 * q4 + 3] = c4[3];
+                acc[cb][4 * q4] = c4[0]; acc[cb][4 * q4 + 1] = c4[1];
+                acc[cb][4 * q4 + 2] = c4[2]; acc[cb][4 * q4 + 3] = c4[3];
             }
 #pragma unroll
             for (int t = 0; t < KT; ++t) {
                 const v4i a = *reinterpret_cast<const v4i *>(cur + L::V_OFF + (32 * cb + m) * L::VP + 64 * g + 16 * t);
-                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pk[t], acc, 0, 0, 0);
+                acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pk[t], acc[cb], 0, 0, 0);
             }
-#pragma unroll
-            for (int r = 0; r < 16; ++r) Of[cb][r] = fmaf(Of[cb][r], resc, __int_as_float(acc[r]));
         }
+        // 5. O = e^{m_old - m_new} O + block result
+#pragma unroll
+        for (int cb = 0; cb < DK; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) Of[cb][r] = fmaf(Of[cb][r], resc, __int_as_float(acc[cb][r]));
 
-        wait_vmem();      // this wave's share of the next image (and its bias prefetch) has landed
-        __syncthreads();  // everyone is done with `cur`, and `nxt` is complete
+        __builtin_amdgcn_sched_barrier(0);  // keep the wait at the very end of the block
+        wait_vmem();      // this wave's copies for the next block have landed
+        __syncthreads();  // everyone is done with this block's buffers, the next ones are complete
     };
 
     // ---- prologue ---------------------------------------------------------------
-    dma_image<DK>(imgs, bufA, wave, lane);
+    const char *imgA = bufA + bsel * L::BYTES, *imgB = bufB + bsel * L::BYTES;
+    const char *bA = biasA + wave * 8192, *bB = BIAS_DB ? biasB + wave * 8192 : bA;
+    dma_image<DK>(imgs, lds_offset(imgA), wave, lane);
     if (MODE == BIAS_BF16_VEC) load_bias_vec(0);
-    if (MODE == BIAS_BF16_LDS) dma_bias(0);
+    if (LDS_BIAS) dma_bias(0, lds_offset(bA));
     wait_vmem();
     __syncthreads();
 
     for (int it = 0; it < p.nblk; it += 2) {
-        step(it, bufA, bufB);
-        if (it + 1 < p.nblk) step(it + 1, bufB, bufA);
+        step(it, imgA, lds_offset(imgB), bA, lds_offset(bB));
+        if (it + 1 < p.nblk) step(it + 1, imgB, lds_offset(imgA), bB, lds_offset(bA));
     }
 
     // ---- epilogue: (O - magic * rho) / (255 l) * delta_v, bf16 store -------------
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float l_tot = pair_sum(l_run);
     const float inv = 1.0f / l_tot;
     const float off = PV_MAGIC_F * rho;
     if (q < N) {
@@ -330,14 +370,23 @@ __global__ __launch_bounds__(FUSED_THREADS, 2) void fused_kernel(const FusedPara
 
 template <int DK>
 int launch_fused_dk(const FusedParams &p, int mode, hipStream_t stream) {
-    const dim3 grid((unsigned)(((p.total_wg + 7) / 8) * 8)), block(FUSED_THREADS);
+    const dim3 grid((unsigned)(((p.total_wg + 7) / 8) * 8));
+    const dim3 block(FUSED_THREADS * p.nb);
+    if (p.nb == 2) {
+        if constexpr (DK <= 2) {
+            if (mode != BIAS_BF16_LDS) return BINATTN_ERR_DTYPE;
+            hipLaunchKernelGGL((fused_kernel<DK, BIAS_BF16_LDS, 2>), grid, block, 0, stream, p);
+            return check_launch();
+        }
+        return BINATTN_ERR_SHAPE;
+    }
     switch (mode) {
-#define CASE(M) case M: hipLaunchKernelGGL((fused_kernel<DK, M>), grid, block, 0, stream, p); break;
+#define CASE(M) case M: hipLaunchKernelGGL((fused_kernel<DK, M, 1>), grid, block, 0, stream, p); break;
         CASE(BIAS_NONE) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC)
 #undef CASE
         case BIAS_BF16_LDS:
             if constexpr (DK <= 3) {
-                hipLaunchKernelGGL((fused_kernel<DK, BIAS_BF16_LDS>), grid, block, 0, stream, p);
+                hipLaunchKernelGGL((fused_kernel<DK, BIAS_BF16_LDS, 1>), grid, block, 0, stream, p);
                 break;
             }
             return BINATTN_ERR_SHAPE;

@@ -34,7 +34,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void logits_fp4_kernel(
     using L = Image<DK>;
     __shared__ __attribute__((aligned(1024))) char buf[L::BYTES];
     const int rb = blockIdx.x % nrb, bh = blockIdx.x / nrb;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int m = lane & 31, g = lane >> 5;
     const int r = rb * BR + wave * ROWS_PER_WAVE + m;  // row inside [0, nrows)
     const int q = min(row_begin + r, N - 1);
@@ -45,7 +45,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void logits_fp4_kernel(
     int32_t *orow = logits + ((int64_t)bh * nrows + r) * N;
     for (int blk = 0; blk < nblk; ++blk) {
         __syncthreads();  // previous block's reads are done
-        dma_image<DK>(imgs + (int64_t)blk * L::BYTES, buf, wave, lane);
+        dma_image<DK>(imgs + (int64_t)blk * L::BYTES, lds_offset(buf), wave, lane);
         wait_vmem();
         __syncthreads();
 #pragma unroll
