@@ -96,6 +96,12 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     const int q = rb * BR + wave * ROWS_PER_WAVE + m;  // this lane's query row
     const int qc = min(q, N - 1);                      // clamped for loads
 
+    // Start the copies of the first block before anything else is fetched.
+    const char *imgs = p.img + (int64_t)bh * p.nblk * L::BYTES;
+    const char *imgA = bufA + bsel * L::BYTES, *imgB = bufB + bsel * L::BYTES;
+    const char *bA = biasA + wave * 8192, *bB = BIAS_DB ? biasB + wave * 8192 : bA;
+    dma_image<DK>(imgs, lds_offset(imgA), wave, lane);
+
     // Logit multiplier alpha of Eq. 6.  Its sign goes into the Q operand and a
     // vanishing alpha clears the Q operand, so that the loop can assume alpha > 0.
     float alpha = p.scale;
@@ -111,8 +117,6 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     load_q_operand<DK2>(p.q_bits + ((int64_t)bh * N + qc) * ((d + 31) / 32), (d + 31) / 32, d, g,
                         a_neg, a_zero, qB);
 
-    const char *imgs = p.img + (int64_t)bh * p.nblk * L::BYTES;
-
     // ---- bias access ----------------------------------------------------------
     const int bsb = (MODE == BIAS_F32_VEC) ? 4 : 2;  // bytes per element
     const char *brow = nullptr;                      // this lane's bias row (register modes)
@@ -121,21 +125,26 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
                ((int64_t)b * p.bs.b + (int64_t)h * p.bs.h + (int64_t)qc * p.bs.n) * bsb;
     // BIAS_BF16_LDS: the tile is fetched with full-cache-line requests (8 lanes cover the
     // 128 bytes of one row segment) straight into LDS.  Copy instruction (rg, gh) moves rows
-    // 8 rg + [0, 8) x keys 64 gh + [0, 64); lane 8 r + s fetches 16-byte chunk (s ^ r) of row
-    // r, so that chunk c of row r lands at 128 r + 16 (c ^ r): the later 16-byte reads of 8
-    // consecutive rows at one chunk index hit 8 different bank groups.
+    // 8 rg + [0, 8) x keys 64 gh + [0, 64); lane 8 r' + s fetches 16-byte chunk c = s ^ r of
+    // row r = r' ^ (rg & 1), so that chunk c of row r lands at 128 (r ^ (rg & 1)) + 16 (c ^ r):
+    // the later 16-byte reads of 16 consecutive rows (two row groups) at one chunk index hit
+    // 16 different 16-byte bank groups of the 256-byte LDS row.
     // A wave copies RGW of the four 8-row groups of its 32-row tile: all four when the
     // tile is its own (NB = 1), two when the tile is shared with the other batch entry.
     constexpr int RGW = 4 / NB;
     const char *bsrc[RGW];
-    const int dma_c = (lane & 7) ^ (lane >> 3);
+    int dma_c[RGW];  // key chunk this lane fetches, per row group
 #pragma unroll
     for (int j = 0; j < RGW; ++j) {
         bsrc[j] = nullptr;
+        dma_c[j] = 0;
         if (LDS_BIAS) {
-            const int row = min(rb * BR + wave * ROWS_PER_WAVE + 8 * (RGW * bsel + j) + (lane >> 3), N - 1);
+            const int rg = RGW * bsel + j;
+            const int r = (lane >> 3) ^ (rg & 1);
+            dma_c[j] = (lane & 7) ^ r;
+            const int row = min(rb * BR + wave * ROWS_PER_WAVE + 8 * rg + r, N - 1);
             bsrc[j] = static_cast<const char *>(p.bias) +
-                      ((int64_t)b * p.bs.b + (int64_t)h * p.bs.h + (int64_t)row * p.bs.n) * 2 + 16 * dma_c;
+                      ((int64_t)b * p.bs.b + (int64_t)h * p.bs.h + (int64_t)row * p.bs.n) * 2 + 16 * dma_c[j];
         }
     }
     auto dma_bias = [&](int blk, unsigned region) {  // region: LDS offset of this wave's 8 KiB tile
@@ -143,7 +152,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         for (int j = 0; j < RGW; ++j)
 #pragma unroll
             for (int gh = 0; gh < 2; ++gh) {
-                const int key0 = blk * BV + 64 * gh + 8 * dma_c;
+                const int key0 = blk * BV + 64 * gh + 8 * dma_c[j];
                 if (key0 + 8 <= N)
                     dma16(bsrc[j] + (blk * BV + 64 * gh) * 2, region + ((RGW * bsel + j) * 2 + gh) * 1024);
             }
@@ -222,10 +231,13 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         // 0. start the copies of the next block
         if (more) dma_image<DK>(imgs + (int64_t)(it + 1) * L::BYTES, nxt, wave, lane);
         if (BIAS_DB && more) dma_bias(it + 1, bnxt);
+        // last block: the idle image buffer receives delta_v for the epilogue
+        if (!more && wave == 0 && lane < DKP / 4)
+            dma16(p.delta + (int64_t)bh * DKP + 4 * lane, nxt);
 
         // 1. all LDS reads of the logit phase go out together: bias tile, key rows
         if (LDS_BIAS) {
-            const char *row = bcur + ((m >> 3) * 2 + g) * 1024 + 128 * (m & 7);
+            const char *row = bcur + ((m >> 3) * 2 + g) * 1024 + 128 * ((m & 7) ^ ((m >> 3) & 1));
 #pragma unroll
             for (int i = 0; i < 8; ++i) braw[i] = *reinterpret_cast<const u4v *>(row + 16 * (i ^ (m & 7)));
         }
@@ -331,9 +343,6 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     };
 
     // ---- prologue ---------------------------------------------------------------
-    const char *imgA = bufA + bsel * L::BYTES, *imgB = bufB + bsel * L::BYTES;
-    const char *bA = biasA + wave * 8192, *bB = BIAS_DB ? biasB + wave * 8192 : bA;
-    dma_image<DK>(imgs, lds_offset(imgA), wave, lane);
     if (MODE == BIAS_BF16_VEC) load_bias_vec(0);
     if (LDS_BIAS) dma_bias(0, lds_offset(bA));
     wait_vmem();
@@ -350,7 +359,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     const float off = PV_MAGIC_F * rho;
     if (q < N) {
         uint16_t *orow = p.out + (int64_t)b * p.os.b + (int64_t)h * p.os.h + (int64_t)q * p.os.n;
-        const float *dl = p.delta + (int64_t)bh * DKP;
+        const float *dl = reinterpret_cast<const float *>(((p.nblk - 1) & 1) ? imgA : imgB);
 #pragma unroll
         for (int cb = 0; cb < DK; ++cb)
 #pragma unroll

@@ -53,10 +53,21 @@ __device__ __forceinline__ float pack_tile(const uint16_t *__restrict__ xb, int6
     __syncthreads();
     uint8_t *bytes = reinterpret_cast<uint8_t *>(words);
     float asum = 0.0f;
-    for (int e = threadIdx.x; e < ntok * C16; e += PACK_THREADS) {
-        const int tok = e / C16, c = e % C16;
-        const u4p v = *reinterpret_cast<const u4p *>(xb + (int64_t)(n0 + tok) * stride_n + 8 * c);
-        bytes[tok * (4 * W) + c] = (uint8_t)sign_bits8(make_uint4(v[0], v[1], v[2], v[3]), asum);
+    // all loads of this thread go out before the first is used (the tile is latency-bound)
+    constexpr int PER = (PACK_TOKENS * C16 + PACK_THREADS - 1) / PACK_THREADS;
+    u4p v[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int e = threadIdx.x + k * PACK_THREADS;
+        if (e < ntok * C16)
+            v[k] = *reinterpret_cast<const u4p *>(xb + (int64_t)(n0 + e / C16) * stride_n + 8 * (e % C16));
+    }
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int e = threadIdx.x + k * PACK_THREADS;
+        if (e < ntok * C16)
+            bytes[(e / C16) * (4 * W) + (e % C16)] =
+                (uint8_t)sign_bits8(make_uint4(v[k][0], v[k][1], v[k][2], v[k][3]), asum);
     }
     __syncthreads();
     for (int i = threadIdx.x; i < ntok * W; i += PACK_THREADS) ob[i] = words[i];

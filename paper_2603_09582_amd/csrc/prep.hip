@@ -83,11 +83,22 @@ __device__ __forceinline__ float absmax_rows(const uint16_t *__restrict__ vb, in
         float m[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) m[i] = 0.0f;
-        for (int n = n0 + r0; n < n1; n += RT) {
-            float f[8];
-            unpack8(*reinterpret_cast<const u4 *>(vb + (int64_t)n * stride_n + 8 * c), f);
+        // four rows per trip, their loads issued together (the loop is latency-bound)
+        const u4 zero4 = {0u, 0u, 0u, 0u};
+        for (int n = n0 + r0; n < n1; n += 4 * RT) {
+            u4 w[4];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) m[i] = fmaxf(m[i], fabsf(f[i]));
+            for (int k = 0; k < 4; ++k)
+                w[k] = (n + k * RT < n1)
+                           ? *reinterpret_cast<const u4 *>(vb + (int64_t)(n + k * RT) * stride_n + 8 * c)
+                           : zero4;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float f[8];
+                unpack8(w[k], f);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) m[i] = fmaxf(m[i], fabsf(f[i]));
+            }
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) smax[r0 * D + 8 * c + i] = m[i];
@@ -104,32 +115,61 @@ __device__ __forceinline__ float delta_of_absmax(float a) {
     return (a == 0.0f) ? 1.0f : __fdiv_rn(a, 127.0f);
 }
 
+// Eq. 7: code = round-to-nearest-even(v / delta), clamped to [-127, 127], where the
+// quotient is the IEEE fp32 one.  v * (1 / delta) is within 2.3e-5 of that quotient
+// (|v / delta| <= 127), so its rounding is already decided unless it sits that close
+// to a half-integer; only then (or if 1 / delta overflowed) is the exact division needed.
+__device__ __forceinline__ float quant_code(float v, float delta, float rcp_delta) {
+    const float t = v * rcp_delta;
+    float q = rintf(t);
+    if (!(fabsf(t) < 200.0f) || fabsf(fabsf(t - q) - 0.5f) < 1e-4f) q = rintf(__fdiv_rn(v, delta));
+    return fminf(fmaxf(q, -127.0f), 127.0f);
+}
+
 // Key block `blk` of one head: codes (channel-major) and the accumulator seeds
 // into the block image.  sdelta (LDS) holds the head's per-channel scales;
 // tile is LDS scratch of 128 * (BV + 16) bytes.
 template <int C16>
 __device__ __forceinline__ void quant_v_block(const uint16_t *__restrict__ vb, int64_t stride_n,
                                               int N, int DKP, int blk, const float *sdelta,
-                                              int8_t *tile, int v_off, int cs_off,
-                                              char *__restrict__ dst) {
+                                              const float *srcp, int8_t *tile, int v_off,
+                                              int cs_off, char *__restrict__ dst) {
     constexpr int LDT = BV + 16;  // LDS row pitch in bytes = Image::VP
     for (int i = threadIdx.x; i < DKP * LDT / 4; i += PREP_THREADS)
         reinterpret_cast<uint32_t *>(tile)[i] = 0u;
     __syncthreads();
 
+    // One thread per (8-channel chunk, 4 consecutive tokens): consecutive lanes take
+    // consecutive token quads, so the transposed 4-byte LDS writes fall into
+    // consecutive banks.
     const int j0 = blk * BV;
     const int nrow = min(BV, N - j0);
-    for (int e = threadIdx.x; e < nrow * C16; e += PREP_THREADS) {
-        const int jl = e / C16, c = e % C16;
-        float f[8];
-        unpack8(*reinterpret_cast<const u4 *>(vb + (int64_t)(j0 + jl) * stride_n + 8 * c), f);
+    for (int e = threadIdx.x; e < C16 * (BV / 4); e += PREP_THREADS) {
+        const int c = e / (BV / 4), jq = e % (BV / 4);
+        unsigned packed[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            // Eq. 7: code = round-to-nearest-even(v / delta), clamped to [-127, 127]
-            float q = rintf(__fdiv_rn(f[i], sdelta[8 * c + i]));
-            q = fminf(fmaxf(q, -127.0f), 127.0f);
-            tile[(8 * c + i) * LDT + jl] = (int8_t)(int)q;
+        for (int i = 0; i < 8; ++i) packed[i] = 0u;
+        u4 w[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int jl = min(4 * jq + k, nrow - 1);  // clamped; rows beyond nrow are dropped below
+            w[k] = *reinterpret_cast<const u4 *>(vb + (int64_t)(j0 + jl) * stride_n + 8 * c);
         }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (4 * jq + k < nrow) {
+                float f[8];
+                unpack8(w[k], f);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float q = quant_code(f[i], sdelta[8 * c + i], srcp[8 * c + i]);
+                    packed[i] |= ((unsigned)(int)q & 0xFFu) << (8 * k);
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            *reinterpret_cast<unsigned *>(tile + (8 * c + i) * LDT + 4 * jq) = packed[i];
     }
     __syncthreads();
 
@@ -159,30 +199,33 @@ __global__ __launch_bounds__(PREP_THREADS) void v_absmax_kernel(const uint16_t *
     if (threadIdx.x < 8 * C16) amax[((int64_t)bh * nchunk + chunk) * DKP + threadIdx.x] = a;
 }
 
-// Long sequences, step 2: one key block of one head.
+// Longer sequences, step 2: one key block of one head (V codes and, if k_bits is
+// not null, the key operand).
 template <int C16>
-__global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(const uint16_t *__restrict__ v,
-                                                               Strides3 vs, int H, int N, int DKP,
-                                                               int nchunk, int nblk,
-                                                               const float *__restrict__ amax,
-                                                               float *__restrict__ delta,
-                                                               int img_bytes, int v_off, int cs_off,
-                                                               char *__restrict__ img) {
-    __shared__ float sdelta[8 * C16];
+__global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(
+    const uint16_t *__restrict__ v, Strides3 vs, const uint32_t *__restrict__ k_bits, int H, int N,
+    int d, int DKP, int nchunk, int nblk, const float *__restrict__ amax, float *__restrict__ delta,
+    int img_bytes, int KP, int v_off, int cs_off, char *__restrict__ img) {
+    __shared__ float sdelta[8 * C16], srcp[8 * C16];
     __shared__ __attribute__((aligned(16))) int8_t tile[128 * (BV + 16)];
     const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
     const int b = bh / H, h = bh % H;
     const uint16_t *vb = v + (int64_t)b * vs.b + (int64_t)h * vs.h;
+    char *dst = img + ((int64_t)bh * nblk + blk) * img_bytes;
+    if (k_bits != nullptr) {
+        const int W = (d + 31) / 32;
+        expand_k_block(k_bits + (int64_t)bh * N * W, N, d, W, blk, KP, dst);
+    }
     if (threadIdx.x < 8 * C16) {
         float a = 0.0f;
         for (int i = 0; i < nchunk; ++i)
             a = fmaxf(a, amax[((int64_t)bh * nchunk + i) * DKP + threadIdx.x]);
         const float dl = delta_of_absmax(a);
         sdelta[threadIdx.x] = dl;
+        srcp[threadIdx.x] = __fdiv_rn(1.0f, dl);
         if (blk == 0) delta[(int64_t)bh * DKP + threadIdx.x] = dl;
     }
-    quant_v_block<C16>(vb, vs.n, N, DKP, blk, sdelta, tile, v_off, cs_off,
-                       img + ((int64_t)bh * nblk + blk) * img_bytes);
+    quant_v_block<C16>(vb, vs.n, N, DKP, blk, sdelta, srcp, tile, v_off, cs_off, dst);
 }
 
 // Short sequences: everything for one key block of one head in ONE launch.  Every
@@ -195,7 +238,7 @@ __global__ __launch_bounds__(PREP_THREADS) void prep_block_kernel(
     int d, int DKP, int nblk, float *__restrict__ delta, int img_bytes, int KP, int v_off, int cs_off,
     char *__restrict__ img) {
     __shared__ float smax[(PREP_THREADS / C16) * 8 * C16];
-    __shared__ float sdelta[8 * C16];
+    __shared__ float sdelta[8 * C16], srcp[8 * C16];
     __shared__ __attribute__((aligned(16))) int8_t tile[128 * (BV + 16)];
     const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
     const int b = bh / H, h = bh % H;
@@ -207,9 +250,10 @@ __global__ __launch_bounds__(PREP_THREADS) void prep_block_kernel(
     if (threadIdx.x < 8 * C16) {
         const float dl = delta_of_absmax(a);
         sdelta[threadIdx.x] = dl;
+        srcp[threadIdx.x] = __fdiv_rn(1.0f, dl);
         if (blk == 0) delta[(int64_t)bh * DKP + threadIdx.x] = dl;
     }
-    quant_v_block<C16>(vb, vs.n, N, DKP, blk, sdelta, tile, v_off, cs_off, dst);
+    quant_v_block<C16>(vb, vs.n, N, DKP, blk, sdelta, srcp, tile, v_off, cs_off, dst);
 }
 
 // Codes and delta from the private layout into [B,H,N,d] / [B,H,d].
@@ -243,8 +287,9 @@ int launch_expand_k(const uint32_t *k_bits, const Shape &s, char *ws, const Work
     return check_launch();
 }
 
-// Sequences up to this many key blocks take the single-launch path.
-constexpr int PREP_FUSED_MAX_BLOCKS = 16;
+// Sequences up to this many key blocks take the single-launch path (every workgroup
+// recomputes the head's absmax); longer ones take absmax partials + one more launch.
+constexpr int PREP_FUSED_MAX_BLOCKS = 2;
 
 template <int C16>
 static void launch_quant_v_t(const void *v, Strides3 vs, const uint32_t *k_bits, const Shape &s,
@@ -263,11 +308,8 @@ static void launch_quant_v_t(const void *v, Strides3 vs, const uint32_t *k_bits,
     hipLaunchKernelGGL(v_absmax_kernel<C16>, dim3((unsigned)s.nchunk * s.BH), dim3(PREP_THREADS),
                        0, stream, vp, vs, s.H, s.N, s.DKP, s.nchunk, amax);
     hipLaunchKernelGGL(v_quant_kernel<C16>, dim3((unsigned)s.nblk * s.BH), dim3(PREP_THREADS), 0,
-                       stream, vp, vs, s.H, s.N, s.DKP, s.nchunk, s.nblk, amax, delta, w.img_bytes,
-                       v_off, cs_off, ws + w.img);
-    if (k_bits != nullptr)
-        hipLaunchKernelGGL(expand_k_kernel, dim3((unsigned)s.nblk * s.BH), dim3(PREP_THREADS), 0,
-                           stream, k_bits, s.N, s.d, s.W, s.nblk, w.img_bytes, KP, ws + w.img);
+                       stream, vp, vs, k_bits, s.H, s.N, s.d, s.DKP, s.nchunk, s.nblk, amax, delta,
+                       w.img_bytes, KP, v_off, cs_off, ws + w.img);
 }
 
 // V quantisation and (if k_bits is not null) the key operand into the block images.
