@@ -37,26 +37,26 @@ constexpr unsigned FP4_PLUS1 = 0x2u, FP4_MINUS1 = 0xAu;
 
 // 8 sign bits -> 8 FP4 nibbles (bit i -> nibble i): +1.0 where set, -1.0 where clear.
 __device__ __forceinline__ unsigned fp4_pm1_from_bits8(unsigned b) {
-    unsigned s = 0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) s |= ((b >> i) & 1u) << (4 * i);
-    return 0xAAAAAAAAu - (s << 3);  // 0xA - 8 = 0x2 where the bit is set
+    unsigned x = (b | (b << 12)) & 0x000F000Fu;  // 4 bits per half word
+    x = (x | (x << 6)) & 0x03030303u;            // 2 bits per byte
+    x = (x | (x << 3)) & 0x11111111u;            // 1 bit per nibble, at its lowest position
+    return 0xAAAAAAAAu - (x << 3);               // 0xA - 8 = 0x2 where the bit is set
 }
 
 // B operand of the QK tile for this lane's query row: FP4 codes of channels
-// 64 s + 32 g + [0, 32) in 16 bytes, zero beyond d.  `flip` negates the row,
-// `zero` clears it (used for a non-positive or vanishing logit multiplier).
+// 64 s + 32 g + [0, 32) in 16 bytes, zero beyond d.  q_words: the row's sign words
+// (zero-filled up to 2 * DK2).  `flip` negates the row, `zero` clears it (used for a
+// non-positive or vanishing logit multiplier).
 template <int DK2>
-__device__ __forceinline__ void load_q_operand(const uint32_t *__restrict__ q_words, int W, int d,
-                                               int g, bool flip, bool zero, v4i qB[DK2]) {
+__device__ __forceinline__ void load_q_operand(const unsigned q_words[2 * DK2], int d, int g,
+                                               bool flip, bool zero, v4i qB[DK2]) {
 #pragma unroll
     for (int s = 0; s < DK2; ++s) {
-        const int w = 2 * s + g;
-        unsigned word = w < W ? q_words[w] : 0u;
+        unsigned word = g ? q_words[2 * s + 1] : q_words[2 * s];
         if (flip) word = ~word;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int c0 = 32 * w + 8 * i;
+            const int c0 = 32 * (2 * s + g) + 8 * i;
             qB[s][i] = (c0 < d && !zero) ? (int)fp4_pm1_from_bits8((word >> (8 * i)) & 0xFFu) : 0;
         }
     }
@@ -69,7 +69,8 @@ __device__ __forceinline__ void load_k_operand(const char *img, int t, int m, in
     using L = Image<DK>;
 #pragma unroll
     for (int s = 0; s < L::DK2; ++s)
-        ka[s] = *reinterpret_cast<const v4i *>(img + L::K_OFF + (32 * t + m) * L::KP + 32 * s + 16 * g);
+        ka[s] = *reinterpret_cast<const v4i *>(img + L::K_OFF + (32 * t + m) * L::KP +
+                                               16 * k_chunk(m, 2 * s + g, L::KP));
 }
 
 // QK tile: for this lane's query, register r of the result is
@@ -105,7 +106,7 @@ __device__ __forceinline__ unsigned lds_offset(const void *p) {
 __device__ __forceinline__ void dma16(const void *gptr, unsigned lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                  :
-                 : "s"(lds_base), "v"(gptr)
+                 : "s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(gptr)
                  : "memory", "m0");
 }
 

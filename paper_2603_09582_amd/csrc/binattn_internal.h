@@ -45,22 +45,28 @@ inline Shape make_shape(int B, int H, int N, int d) {
 // workspace exactly as the attention kernel wants it in LDS, so that a block is
 // one flat asynchronous copy:
 //   K  [BV positions][KP bytes]  FP4 codes of the +-1 keys (0 beyond d / beyond N),
-//                                32 bytes per 64 channels, rows in MFMA order
-//   VT [DKP channels][VP bytes]  V codes, channel-major, BV key bytes per row
+//                                32 bytes per 64 channels, rows in MFMA order; the
+//                                16-byte chunks of a row are XOR-swizzled (k_chunk)
+//   VT [DKP channels][VP bytes]  V codes, channel-major, BV key bytes per row + 16 pad
 //   CS [DKP] int32               PV_MAGIC + 128 * (sum of the block's V codes)
-// The pitches KP and VP carry 16 bytes of padding: 16-byte reads of 8
-// consecutive rows then fall into 8 different bank groups.
+// Swizzle and padding make the 16-byte reads of 16 consecutive rows fall into 16
+// different 16-byte bank groups of the 256-byte LDS row.
 template <int DK>
 struct Image {
     static constexpr int DK2 = (DK + 1) / 2;       // 64-channel groups of the QK contraction
     static constexpr int DKP = 32 * DK;            // padded channel count of V
-    static constexpr int KP = 32 * DK2 + 16;
+    static constexpr int KP = 32 * DK2;
     static constexpr int VP = BV + 16;
     static constexpr int K_OFF = 0;
     static constexpr int V_OFF = BV * KP;
     static constexpr int CS_OFF = V_OFF + DKP * VP;
     static constexpr int BYTES = (CS_OFF + DKP * 4 + 1023) / 1024 * 1024;
 };
+
+// Where 16-byte chunk `chunk` (of KP / 16) of K row `pos` is stored inside the row.
+__host__ __device__ inline int k_chunk(int pos, int chunk, int KP) {
+    return KP == 32 ? (chunk ^ ((pos >> 3) & 1)) : (chunk ^ ((pos >> 2) & 3));
+}
 
 inline int image_bytes(int DK) {
     switch (DK) {

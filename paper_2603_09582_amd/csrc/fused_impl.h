@@ -47,10 +47,12 @@ constexpr float LOG2_255_F = 7.99435343685885793770f;
 __device__ __forceinline__ float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
 
-__device__ __forceinline__ unsigned f32_to_bf16_rne(float f) {
-    unsigned u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // keep NaN a NaN
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+// two fp32 -> two bf16 in one dword, round to nearest even (v_cvt_pk_bf16_f32)
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+    const f2v v = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
 }
 
 // NB = batch entries per workgroup.  NB = 2 (only with BIAS_BF16_LDS and a bias shared
@@ -58,9 +60,20 @@ __device__ __forceinline__ unsigned f32_to_bf16_rne(float f) {
 // 8-wave workgroup: waves 0-3 work on entry 2 bp, waves 4-7 on entry 2 bp + 1, and
 // both read the SAME bias tile from LDS, so the bias - the dominant HBM stream of
 // long sequences - is fetched once per pair and can be double-buffered.
+//
+// With NB = 1 the grid is persistent: a workgroup walks work items v, v + G, v + 2G, ...
+// (G = grid size) and treats all their key blocks as ONE stream, so the asynchronous
+// copies for the first block of the next item are already in flight during the last
+// block of the current one; only the very first block of a workgroup waits for memory.
+// That pays for short sequences (few blocks per item).  NB = 2 is only used for long
+// sequences, where the item switch is rare and its bookkeeping at the start of every
+// block (all waves of a workgroup pass it together, right after the barrier, so it is
+// not hidden behind another wave's arithmetic) costs more than it saves: there a
+// workgroup computes one item.
 template <int DK, int MODE, int NB>
 __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const FusedParams p) {
     using L = Image<DK>;
+    constexpr bool PERSIST = NB == 1;
     constexpr int DKP = 32 * DK;
     constexpr int DK2 = L::DK2;
     constexpr bool LDS_BIAS = MODE == BIAS_BF16_LDS;
@@ -75,54 +88,49 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     // NB = 1: one region per wave, private to it.  NB = 2: two buffers shared by the pair.
     __shared__ __attribute__((aligned(1024))) char biasA[LDS_BIAS ? 4 * 8192 : 1024];
     __shared__ __attribute__((aligned(1024))) char biasB[BIAS_DB ? 4 * 8192 : 1024];
+    // delta_v of the current item (two copies: consecutive items alternate)
+    __shared__ __attribute__((aligned(16))) float sdelta[2][NB][DKP];
 
-    // Workgroup -> work item.  Consecutive workgroup ids go to different XCDs, so
-    // the id is first turned into (xcd, slot) and work items that share a bias
-    // slab (same head and row block, different batch entry) are given to one XCD
-    // back to back: they then share that slab through the XCD's L2.
-    const int per_xcd = (p.total_wg + 7) >> 3;
-    const int u = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (u >= p.total_wg) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) & 3);  // 32-row group
     const int bsel = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);        // batch entry in the workgroup
-    const int nbp = p.B / NB;
-    const int b = (u % nbp) * NB + bsel;
-    const int rb = (u / nbp) % p.nrb;
-    const int h = u / (nbp * p.nrb);
-    const int bh = b * p.H + h;
-    const int N = p.N, d = p.d;
     const int m = lane & 31, g = lane >> 5;
-    const int q = rb * BR + wave * ROWS_PER_WAVE + m;  // this lane's query row
-    const int qc = min(q, N - 1);                      // clamped for loads
+    const int N = p.N, d = p.d, W = (d + 31) / 32;
+    const int nbp = p.B / NB;
+    const int per_xcd = (p.total_wg + 7) >> 3;
+    const int vmax = 8 * per_xcd;
+    const int bsb = (MODE == BIAS_F32_VEC) ? 4 : 2;  // bytes per bias element
 
-    // Start the copies of the first block before anything else is fetched.
-    const char *imgs = p.img + (int64_t)bh * p.nblk * L::BYTES;
-    const char *imgA = bufA + bsel * L::BYTES, *imgB = bufB + bsel * L::BYTES;
-    const char *bA = biasA + wave * 8192, *bB = BIAS_DB ? biasB + wave * 8192 : bA;
-    dma_image<DK>(imgs, lds_offset(imgA), wave, lane);
+    // Work item v -> (batch, head, row block).  Consecutive ids go to different XCDs, so v
+    // is first turned into (xcd, slot); items that share a bias slab (same head and row
+    // block, different batch entry) are neighbours on one XCD and share it through that
+    // XCD's L2.  The grid size is a multiple of 8, so a workgroup stays on its XCD.
+    struct Item {
+        int b, h, rb, bh;
+        bool valid;
+    };
+    auto decode = [&](int v) -> Item {
+        Item t;
+        const int u = (v & 7) * per_xcd + (v >> 3);
+        t.valid = v < vmax && u < p.total_wg;
+        const int uu = t.valid ? u : 0;
+        t.b = (uu % nbp) * NB + bsel;
+        t.rb = (uu / nbp) % p.nrb;
+        t.h = uu / (nbp * p.nrb);
+        t.bh = t.b * p.H + t.h;
+        return t;
+    };
 
-    // Logit multiplier alpha of Eq. 6.  Its sign goes into the Q operand and a
-    // vanishing alpha clears the Q operand, so that the loop can assume alpha > 0.
-    float alpha = p.scale;
-    if (p.mu_q) alpha *= p.mu_q[bh];
-    if (p.mu_k) alpha *= p.mu_k[bh];
-    const bool a_zero = fabsf(alpha) < 1e-30f;
-    const bool a_neg = alpha < 0.0f;
-    const float a_abs = a_zero ? 1.0f : fabsf(alpha);
-    const float inv_alpha = 1.0f / a_abs;
-    const float a2 = a_abs * LOG2E_F;  // exponent multiplier in base 2
+    int v = blockIdx.x;
+    Item cur = decode(v);
+    if (!cur.valid) return;  // uniform over the workgroup
 
+    // ---- per-item state ---------------------------------------------------------
+    const char *imgs;  // block images of the item's head
+    int q;             // this lane's query row
+    float inv_alpha, a2;
     v4i qB[DK2];
-    load_q_operand<DK2>(p.q_bits + ((int64_t)bh * N + qc) * ((d + 31) / 32), (d + 31) / 32, d, g,
-                        a_neg, a_zero, qB);
-
-    // ---- bias access ----------------------------------------------------------
-    const int bsb = (MODE == BIAS_F32_VEC) ? 4 : 2;  // bytes per element
-    const char *brow = nullptr;                      // this lane's bias row (register modes)
-    if (MODE == BIAS_BF16_VEC || MODE == BIAS_F32_VEC)
-        brow = static_cast<const char *>(p.bias) +
-               ((int64_t)b * p.bs.b + (int64_t)h * p.bs.h + (int64_t)qc * p.bs.n) * bsb;
+    const char *brow = nullptr;  // this lane's bias row (register modes)
     // BIAS_BF16_LDS: the tile is fetched with full-cache-line requests (8 lanes cover the
     // 128 bytes of one row segment) straight into LDS.  Copy instruction (rg, gh) moves rows
     // 8 rg + [0, 8) x keys 64 gh + [0, 64); lane 8 r' + s fetches 16-byte chunk c = s ^ r of
@@ -137,30 +145,80 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
 #pragma unroll
     for (int j = 0; j < RGW; ++j) {
         bsrc[j] = nullptr;
-        dma_c[j] = 0;
-        if (LDS_BIAS) {
-            const int rg = RGW * bsel + j;
-            const int r = (lane >> 3) ^ (rg & 1);
-            dma_c[j] = (lane & 7) ^ r;
-            const int row = min(rb * BR + wave * ROWS_PER_WAVE + 8 * rg + r, N - 1);
-            bsrc[j] = static_cast<const char *>(p.bias) +
-                      ((int64_t)b * p.bs.b + (int64_t)h * p.bs.h + (int64_t)row * p.bs.n) * 2 + 16 * dma_c[j];
-        }
+        dma_c[j] = (lane & 7) ^ (lane >> 3) ^ ((RGW * bsel + j) & 1);
     }
-    auto dma_bias = [&](int blk, unsigned region) {  // region: LDS offset of this wave's 8 KiB tile
+    float m_run, l_run, rho;  // running max (units of T = S / alpha), sum of 255 exp(S - m), rescale sum
+    float Of[DK][16];         // output carry, channel 32 cb + 8 (r/4) + 4 g + r % 4
+
+    // registers fetched ahead for the NEXT item
+    unsigned pend_q[2 * DK2];
+    float pend_muq = 1.0f, pend_muk = 1.0f;
+    auto fetch_item_regs = [&](const Item &t) {
+        const int qc = min(t.rb * BR + wave * ROWS_PER_WAVE + m, N - 1);
+        const uint32_t *qw = p.q_bits + ((int64_t)t.bh * N + qc) * W;
+#pragma unroll
+        for (int w = 0; w < 2 * DK2; ++w) pend_q[w] = w < W ? qw[w] : 0u;
+        pend_muq = p.mu_q ? p.mu_q[t.bh] : 1.0f;
+        pend_muk = p.mu_k ? p.mu_k[t.bh] : 1.0f;
+    };
+    // bias pointers of an item (no memory access)
+    auto bias_row_ptr = [&](const Item &t) -> const char * {
+        const int qc = min(t.rb * BR + wave * ROWS_PER_WAVE + m, N - 1);
+        return static_cast<const char *>(p.bias) +
+               ((int64_t)t.b * p.bs.b + (int64_t)t.h * p.bs.h + (int64_t)qc * p.bs.n) * bsb;
+    };
+    auto bias_dma_ptr = [&](const Item &t, int j) -> const char * {
+        const int rg = RGW * bsel + j;
+        const int r = (lane >> 3) ^ (rg & 1);
+        const int row = min(t.rb * BR + wave * ROWS_PER_WAVE + 8 * rg + r, N - 1);
+        return static_cast<const char *>(p.bias) +
+               ((int64_t)t.b * p.bs.b + (int64_t)t.h * p.bs.h + (int64_t)row * p.bs.n) * 2 + 16 * dma_c[j];
+    };
+    auto image_ptr = [&](const Item &t) -> const char * {
+        return p.img + (int64_t)t.bh * p.nblk * L::BYTES;
+    };
+    // turn the fetched registers into the item's state
+    auto begin_item = [&](const Item &t) {
+        imgs = image_ptr(t);
+        q = t.rb * BR + wave * ROWS_PER_WAVE + m;
+        // Logit multiplier alpha of Eq. 6.  Its sign goes into the Q operand and a vanishing
+        // alpha clears the Q operand, so that the loop can assume alpha > 0.
+        const float alpha = p.scale * pend_muq * pend_muk;
+        const bool a_zero = fabsf(alpha) < 1e-30f;
+        const bool a_neg = alpha < 0.0f;
+        const float a_abs = a_zero ? 1.0f : fabsf(alpha);
+        inv_alpha = 1.0f / a_abs;
+        a2 = a_abs * LOG2E_F;  // exponent multiplier in base 2
+        load_q_operand<DK2>(pend_q, d, g, a_neg, a_zero, qB);
+        if (MODE == BIAS_BF16_VEC || MODE == BIAS_F32_VEC) brow = bias_row_ptr(t);
+        if (LDS_BIAS) {
+#pragma unroll
+            for (int j = 0; j < RGW; ++j) bsrc[j] = bias_dma_ptr(t, j);
+        }
+        m_run = -INFINITY;
+        l_run = 0.0f;
+        rho = 0.0f;
+#pragma unroll
+        for (int cb = 0; cb < DK; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) Of[cb][r] = 0.0f;
+    };
+
+    // ---- bias access ----------------------------------------------------------
+    auto dma_bias = [&](const char *const src[RGW], int blk, unsigned region) {  // region: LDS offset of the 8 KiB tile
 #pragma unroll
         for (int j = 0; j < RGW; ++j)
 #pragma unroll
             for (int gh = 0; gh < 2; ++gh) {
                 const int key0 = blk * BV + 64 * gh + 8 * dma_c[j];
                 if (key0 + 8 <= N)
-                    dma16(bsrc[j] + (blk * BV + 64 * gh) * 2, region + ((RGW * bsel + j) * 2 + gh) * 1024);
+                    dma16(src[j] + (blk * BV + 64 * gh) * 2, region + ((RGW * bsel + j) * 2 + gh) * 1024);
             }
     };
     u4v braw[8];  // the 64 bf16 bias values of this lane for the current block
-    auto load_bias_vec = [&](int blk) {  // BIAS_BF16_VEC: registers straight from global memory
+    auto load_bias_vec = [&](const char *row, int blk) {  // BIAS_BF16_VEC: registers straight from global memory
         const int k0 = blk * BV + 64 * g;
-        const uint16_t *src = reinterpret_cast<const uint16_t *>(brow) + k0;
+        const uint16_t *src = reinterpret_cast<const uint16_t *>(row) + k0;
         if (blk * BV + BV <= N) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) braw[i] = *reinterpret_cast<const u4v_a2 *>(src + 8 * i);
@@ -214,45 +272,85 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         return bt;
     };
 
-    float m_run = -INFINITY;  // running row maximum, in units of T = S / alpha
-    float l_run = 0.0f;       // running sum of 255 * exp(S - m) over this lane's keys
-    float rho = 0.0f;         // running sum of rescale products (see step 5 above)
-    float Of[DK][16];         // output carry, channel 32 cb + 8 (r/4) + 4 g + r % 4
+    // ---- epilogue of an item: (O - magic * rho) / (255 l) * delta_v, bf16 store ----
+    // A lane holds 4 consecutive channels per (cb, q4) and its partner lane ^ 32 the next 4.
+    // One permlane32 swap per dword regroups two such quads so that the lower lane owns 8
+    // consecutive channels of quad 2k and the upper lane those of quad 2k + 1: 16-byte stores.
+    auto finish_item = [&](const Item &t, const float *dl) {
+        // The epilogue runs once per item; the empty statement below ties its inputs to this
+        // point so that none of its arithmetic is hoisted into the per-block path.
+        asm volatile("" : "+v"(l_run), "+v"(rho), "+v"(dl));
+        const float l_tot = pair_sum(l_run);
+        const float inv = 1.0f / l_tot;
+        const float off = PV_MAGIC_F * rho;
+        uint16_t *orow = p.out + (int64_t)t.b * p.os.b + (int64_t)t.h * p.os.h + (int64_t)min(q, N - 1) * p.os.n;
 #pragma unroll
-    for (int cb = 0; cb < DK; ++cb)
+        for (int cb = 0; cb < DK; ++cb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) Of[cb][r] = 0.0f;
+            for (int k = 0; k < 2; ++k) {
+                unsigned w[2][2];  // [quad 2k / 2k+1][dword]
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int q4 = 2 * k + e;
+                    const float4 d4 = *reinterpret_cast<const float4 *>(dl + 32 * cb + 8 * q4 + 4 * g);
+                    w[e][0] = pack_bf16x2((Of[cb][4 * q4 + 0] - off) * inv * d4.x,
+                                          (Of[cb][4 * q4 + 1] - off) * inv * d4.y);
+                    w[e][1] = pack_bf16x2((Of[cb][4 * q4 + 2] - off) * inv * d4.z,
+                                          (Of[cb][4 * q4 + 3] - off) * inv * d4.w);
+                }
+                // lower lanes: {own quad 2k, partner's quad 2k}; upper: {partner's 2k+1, own 2k+1}
+                const auto s0 = __builtin_amdgcn_permlane32_swap(w[0][0], w[1][0], false, false);
+                const auto s1 = __builtin_amdgcn_permlane32_swap(w[0][1], w[1][1], false, false);
+                const int c = 32 * cb + 16 * k + 8 * g;  // first of this lane's 8 channels
+                if (q < N && c < d)
+                    *reinterpret_cast<u4v *>(orow + c) = u4v{s0[0], s1[0], s0[1], s1[1]};
+            }
+    };
 
-    // One key/value block: compute on the image at `cur`, prefetch block it + 1 into the
-    // image buffer at LDS offset `nxt`.  bcur / bnxt: this wave's bias tile region now and
-    // for the next block (the same region unless the bias is double-buffered).
-    auto step = [&](int it, const char *cur, unsigned nxt, const char *bcur, unsigned bnxt) {
-        const bool more = it + 1 < p.nblk;
-        // 0. start the copies of the next block
-        if (more) dma_image<DK>(imgs + (int64_t)(it + 1) * L::BYTES, nxt, wave, lane);
-        if (BIAS_DB && more) dma_bias(it + 1, bnxt);
-        // last block: the idle image buffer receives delta_v for the epilogue
-        if (!more && wave == 0 && lane < DKP / 4)
-            dma16(p.delta + (int64_t)bh * DKP + 4 * lane, nxt);
+    // ---- stream position --------------------------------------------------------
+    int it = 0;        // key block inside the current item
+    int parity = 0;    // items alternate between the two delta_v copies
+    Item nxt = decode(PERSIST ? v + gridDim.x : vmax);
+
+    // One key/value block of the stream: compute block `it` of item `cur` from the image at
+    // `ibuf` (and bias tile at `bbuf`), prefetch the next block of the stream into the LDS
+    // offsets `inxt` / `bnxt`.  Returns false after the last block of the last item.
+    auto step = [&](const char *ibuf, unsigned inxt, const char *bbuf, unsigned bnxt) -> bool {
+        const bool last = it + 1 == p.nblk;          // last block of this item
+        const bool more = !last || (PERSIST && nxt.valid);  // the stream goes on
+        // 0. start the copies for the next block of the stream
+        const bool sw = PERSIST && last;  // ... which belongs to the next item
+        const char *nimg = sw ? image_ptr(nxt) : imgs + (int64_t)(it + 1) * L::BYTES;
+        const int nblkidx = sw ? 0 : it + 1;
+        const char *nsrc[RGW];
+#pragma unroll
+        for (int j = 0; j < RGW; ++j) nsrc[j] = (LDS_BIAS && sw) ? bias_dma_ptr(nxt, j) : bsrc[j];
+        if (more) dma_image<DK>(nimg, inxt + bsel * L::BYTES, wave, lane);
+        if (BIAS_DB && more) dma_bias(nsrc, nblkidx, bnxt);
+        if (it == 0 && wave == 0 && lane < DKP / 4)  // delta_v of this item, for its epilogue
+            dma16(p.delta + (int64_t)cur.bh * DKP + 4 * lane, lds_offset(&sdelta[parity][bsel][0]));
+        if (sw && nxt.valid) fetch_item_regs(nxt);
 
         // 1. all LDS reads of the logit phase go out together: bias tile, key rows
         if (LDS_BIAS) {
-            const char *row = bcur + ((m >> 3) * 2 + g) * 1024 + 128 * ((m & 7) ^ ((m >> 3) & 1));
+            const char *row = bbuf + ((m >> 3) * 2 + g) * 1024 + 128 * ((m & 7) ^ ((m >> 3) & 1));
 #pragma unroll
             for (int i = 0; i < 8; ++i) braw[i] = *reinterpret_cast<const u4v *>(row + 16 * (i ^ (m & 7)));
         }
         v4i ka[KT][DK2];
 #pragma unroll
-        for (int t = 0; t < KT; ++t) load_k_operand<DK>(cur, t, m, g, ka[t]);
+        for (int t = 0; t < KT; ++t) load_k_operand<DK>(ibuf, t, m, g, ka[t]);
+        __builtin_amdgcn_sched_barrier(0);  // all of them in flight before the first use
         //    T = I + b / alpha
         v16f T[KT];
 #pragma unroll
         for (int t = 0; t < KT; ++t) T[t] = qk_mfma<DK2>(ka[t], qB, bias_tile(it, t));
         __builtin_amdgcn_sched_barrier(0);
-        if (MODE == BIAS_BF16_VEC && more) load_bias_vec(it + 1);  // braw is free again
+        if (MODE == BIAS_BF16_VEC && more)  // braw is free again
+            load_bias_vec(sw ? bias_row_ptr(nxt) : brow, nblkidx);
         if (LDS_BIAS && !BIAS_DB && more) {
-            wait_lds();              // this block's tile has been read into registers
-            dma_bias(it + 1, bnxt);  // refill the wave's own region
+            wait_lds();                       // this block's tile has been read into registers
+            dma_bias(nsrc, nblkidx, bnxt);    // refill the wave's own region
         }
         //    the LDS reads of the P.V phase go out now and land during the exponentials
         v16i acc[DK];
@@ -261,13 +359,13 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         for (int cb = 0; cb < PRE; ++cb) {
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                const v4i c4 = *reinterpret_cast<const v4i *>(cur + L::CS_OFF + 4 * (32 * cb + 8 * q4 + 4 * g));
+                const v4i c4 = *reinterpret_cast<const v4i *>(ibuf + L::CS_OFF + 4 * (32 * cb + 8 * q4 + 4 * g));
                 acc[cb][4 * q4] = c4[0]; acc[cb][4 * q4 + 1] = c4[1];
                 acc[cb][4 * q4 + 2] = c4[2]; acc[cb][4 * q4 + 3] = c4[3];
             }
 #pragma unroll
             for (int t = 0; t < KT; ++t)
-                va[cb][t] = *reinterpret_cast<const v4i *>(cur + L::V_OFF + (32 * cb + m) * L::VP + 64 * g + 16 * t);
+                va[cb][t] = *reinterpret_cast<const v4i *>(ibuf + L::V_OFF + (32 * cb + m) * L::VP + 64 * g + 16 * t);
         }
 
         if (it * BV + BV > N) {  // ragged last block: keys beyond N never count
@@ -321,13 +419,13 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         for (int cb = PRE; cb < DK; ++cb) {
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                const v4i c4 = *reinterpret_cast<const v4i *>(cur + L::CS_OFF + 4 * (32 * cb + 8 * q4 + 4 * g));
+                const v4i c4 = *reinterpret_cast<const v4i *>(ibuf + L::CS_OFF + 4 * (32 * cb + 8 * q4 + 4 * g));
                 acc[cb][4 * q4] = c4[0]; acc[cb][4 * q4 + 1] = c4[1];
                 acc[cb][4 * q4 + 2] = c4[2]; acc[cb][4 * q4 + 3] = c4[3];
             }
 #pragma unroll
             for (int t = 0; t < KT; ++t) {
-                const v4i a = *reinterpret_cast<const v4i *>(cur + L::V_OFF + (32 * cb + m) * L::VP + 64 * g + 16 * t);
+                const v4i a = *reinterpret_cast<const v4i *>(ibuf + L::V_OFF + (32 * cb + m) * L::VP + 64 * g + 16 * t);
                 acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, pk[t], acc[cb], 0, 0, 0);
             }
         }
@@ -340,46 +438,46 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         __builtin_amdgcn_sched_barrier(0);  // keep the wait at the very end of the block
         wait_vmem();      // this wave's copies for the next block have landed
         __syncthreads();  // everyone is done with this block's buffers, the next ones are complete
+
+        if (!last) {
+            ++it;
+            return true;
+        }
+        finish_item(cur, &sdelta[parity][bsel][0]);
+        if (!PERSIST || !nxt.valid) return false;
+        cur = nxt;
+        v += gridDim.x;
+        nxt = decode(v + gridDim.x);
+        begin_item(cur);
+        it = 0;
+        parity ^= 1;
+        return true;
     };
 
-    // ---- prologue ---------------------------------------------------------------
-    if (MODE == BIAS_BF16_VEC) load_bias_vec(0);
-    if (LDS_BIAS) dma_bias(0, lds_offset(bA));
+    // ---- prologue: first block of the first item --------------------------------
+    const char *bA = biasA + wave * 8192, *bB = BIAS_DB ? biasB + wave * 8192 : bA;
+    dma_image<DK>(image_ptr(cur), lds_offset(bufA) + bsel * L::BYTES, wave, lane);
+    fetch_item_regs(cur);
+    begin_item(cur);
+    if (MODE == BIAS_BF16_VEC) load_bias_vec(brow, 0);
+    if (LDS_BIAS) dma_bias(bsrc, 0, lds_offset(bA));
     wait_vmem();
     __syncthreads();
 
-    for (int it = 0; it < p.nblk; it += 2) {
-        step(it, imgA, lds_offset(imgB), bA, lds_offset(bB));
-        if (it + 1 < p.nblk) step(it + 1, imgB, lds_offset(imgA), bB, lds_offset(bA));
-    }
-
-    // ---- epilogue: (O - magic * rho) / (255 l) * delta_v, bf16 store -------------
-    const float l_tot = pair_sum(l_run);
-    const float inv = 1.0f / l_tot;
-    const float off = PV_MAGIC_F * rho;
-    if (q < N) {
-        uint16_t *orow = p.out + (int64_t)b * p.os.b + (int64_t)h * p.os.h + (int64_t)q * p.os.n;
-        const float *dl = reinterpret_cast<const float *>(((p.nblk - 1) & 1) ? imgA : imgB);
-#pragma unroll
-        for (int cb = 0; cb < DK; ++cb)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const int c = 32 * cb + 8 * q4 + 4 * g;
-                if (c < d) {
-                    const float4 d4 = *reinterpret_cast<const float4 *>(dl + c);
-                    const unsigned y0 = f32_to_bf16_rne((Of[cb][4 * q4 + 0] - off) * inv * d4.x);
-                    const unsigned y1 = f32_to_bf16_rne((Of[cb][4 * q4 + 1] - off) * inv * d4.y);
-                    const unsigned y2 = f32_to_bf16_rne((Of[cb][4 * q4 + 2] - off) * inv * d4.z);
-                    const unsigned y3 = f32_to_bf16_rne((Of[cb][4 * q4 + 3] - off) * inv * d4.w);
-                    *reinterpret_cast<uint2 *>(orow + c) = make_uint2(y0 | (y1 << 16), y2 | (y3 << 16));
-                }
-            }
+    const char *imgA = bufA + bsel * L::BYTES, *imgB = bufB + bsel * L::BYTES;
+    for (;;) {
+        if (!step(imgA, lds_offset(bufB), bA, lds_offset(bB))) break;
+        if (!step(imgB, lds_offset(bufA), bB, lds_offset(bA))) break;
     }
 }
 
 template <int DK>
 int launch_fused_dk(const FusedParams &p, int mode, hipStream_t stream) {
-    const dim3 grid((unsigned)(((p.total_wg + 7) / 8) * 8));
+    // NB = 1, persistent grid: as many workgroups as fit on the chip at once (two 4-wave
+    // workgroups per CU, 256 CUs), a multiple of 8 so that a workgroup's items stay on one
+    // XCD; fewer if there is less work.  NB = 2: one workgroup per item.
+    const int needed = ((p.total_wg + 7) / 8) * 8;
+    const dim3 grid((unsigned)(p.nb == 2 || needed < 512 ? needed : 512));
     const dim3 block(FUSED_THREADS * p.nb);
     if (p.nb == 2) {
         if constexpr (DK <= 2) {

@@ -40,7 +40,10 @@ __global__ __launch_bounds__(FUSED_THREADS) void logits_fp4_kernel(
     const int q = min(row_begin + r, N - 1);
     const int W = (d + 31) / 32;
     v4i qB[L::DK2];
-    load_q_operand<L::DK2>(q_bits + ((int64_t)bh * N + q) * W, W, d, g, false, false, qB);
+    unsigned qw[2 * L::DK2];
+#pragma unroll
+    for (int w = 0; w < 2 * L::DK2; ++w) qw[w] = w < W ? q_bits[((int64_t)bh * N + q) * W + w] : 0u;
+    load_q_operand<L::DK2>(qw, d, g, false, false, qB);
     const char *imgs = img + (int64_t)bh * nblk * L::BYTES;
     int32_t *orow = logits + ((int64_t)bh * nrows + r) * N;
     for (int blk = 0; blk < nblk; ++blk) {

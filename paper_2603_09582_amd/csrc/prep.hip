@@ -16,10 +16,10 @@ typedef unsigned u4 __attribute__((ext_vector_type(4)));
 
 // 8 sign bits -> 8 FP4 (e2m1) nibbles: +1.0 (0x2) where set, -1.0 (0xA) where clear.
 __device__ __forceinline__ unsigned fp4_pm1_bits8(unsigned b) {
-    unsigned sp = 0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) sp |= ((b >> i) & 1u) << (4 * i);
-    return 0xAAAAAAAAu - (sp << 3);
+    unsigned x = (b | (b << 12)) & 0x000F000Fu;
+    x = (x | (x << 6)) & 0x03030303u;
+    x = (x | (x << 3)) & 0x11111111u;
+    return 0xAAAAAAAAu - (x << 3);
 }
 
 // Row position inside a key block <-> key offset.  The fused kernel's lane
@@ -49,7 +49,7 @@ __device__ __forceinline__ void expand_k_block(const uint32_t *__restrict__ kb, 
 #pragma unroll
         for (int n = 0; n < 4; ++n)
             o[n] = (8 * n < valid) ? fp4_pm1_bits8((word >> (8 * n)) & 0xFFu) : 0u;
-        *reinterpret_cast<u4 *>(dst + (int64_t)pos * KP + 16 * w) = o;
+        *reinterpret_cast<u4 *>(dst + (int64_t)pos * KP + 16 * k_chunk(pos, w, KP)) = o;
     }
 }
 
