@@ -290,7 +290,15 @@ void ba_oracle_algorithm1_rows(const uint16_t *Q, const uint16_t *K, const uint1
             /* P_hat = exp(S - m_ij); l_ij = e^{m_old - m_new} l + rowsum(P_hat) */
             double resc = exp(m - m_new); /* exp(-inf) = 0 on the first block */
             double rs = 0.0;
-            for (int64_t jj = 0; jj < nb; ++jj) { Pblk[jj] = exp(Sblk[jj] - m_new); rs += Pblk[jj]; }
+            if (m_new == -INFINITY) {
+                /* every key seen so far carries a -inf bias (a mask): exp(-inf - (-inf)) is
+                   undefined in Alg. 1 as printed; a masked key has weight 0 (the limit of
+                   exp(s - m) for s -> -inf at any finite m), so the block adds nothing */
+                resc = 1.0;
+                for (int64_t jj = 0; jj < nb; ++jj) Pblk[jj] = 0.0;
+            } else {
+                for (int64_t jj = 0; jj < nb; ++jj) { Pblk[jj] = exp(Sblk[jj] - m_new); rs += Pblk[jj]; }
+            }
             l = resc * l + rs;
             /* O_ij = IntMatmul(P_hat * 255, V~_j) */
             for (int c = 0; c < d; ++c) blk[c] = 0.0;

@@ -356,6 +356,34 @@ def test_algorithm1_quantised_single_block_equals_definition_and_blocks_stay_clo
     assert np.array_equal(sub, orc.algorithm1_rows(*args, Bv=32, quantise=True)[rows])
 
 
+@pytest.mark.parametrize("Bv", [8, 64, 1000])
+def test_algorithm1_masked_keys_equal_deleted_keys(Bv):
+    # A -inf bias is a mask: the result must be the softmax attention (library routine) over
+    # the remaining keys only, also when whole leading blocks are masked (running max still
+    # -inf) and when a row keeps a single key.  Quantised and global-max forms agree in kind.
+    N, d = 90, 64
+    q, k, v, bias = _head(N, d, 41, bias_std=0.4)
+    masked = np.zeros(N, dtype=bool)
+    masked[:20] = True            # two and a half leading blocks of 8
+    masked[[33, 34, 57, 89]] = True
+    bias[:, masked] = -np.inf
+    keep = ~masked
+    vq, delta = orc.quant_v(v)
+    scale, mq, mk = 0.125, 0.8, 0.9
+    A = orc.algorithm1_rows(q, k, v, bias, scale, mq, mk, vq, delta, Bv=Bv, quantise=False)
+    tq = torch.tensor(np.where(bits_to_f64(q) >= 0, 1.0, -1.0))
+    tk = torch.tensor(np.where(bits_to_f64(k) >= 0, 1.0, -1.0))[keep]
+    logits = (tq @ tk.T) * (scale * mq * mk) + torch.tensor(bias[:, keep].astype(np.float64))
+    want = (torch.softmax(logits, dim=-1) @ torch.tensor(bits_to_f64(v))[keep]).numpy()
+    assert np.isfinite(A).all()
+    assert np.allclose(A, want, rtol=0, atol=1e-12)
+    O = orc.attention_rows(q, k, v, bias, scale, mq, mk, vq, delta, want=("O1", "O2"))
+    assert np.allclose(O["O1"], want, rtol=0, atol=1e-12)
+    Aq = orc.algorithm1_rows(q, k, v, bias, scale, mq, mk, vq, delta, Bv=Bv, quantise=True)
+    assert np.isfinite(Aq).all()
+    assert np.all(np.abs(Aq - O["O2"]) <= 1e-2 + 2e-2 * np.abs(O["O2"]))
+
+
 # --------------------------------------------------------------------------
 # whole-layer driver
 # --------------------------------------------------------------------------
