@@ -28,14 +28,24 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# Algorithmic vector-ALU work per (query, key) pair of the fused kernel, in
-# lane-instructions: int->float of the logit, bias unpack, scale+bias FMA, max,
-# exponent FMA, exp (one transcendental = 4 quarter-rate issue slots on the
-# 16-lane SIMD: measured), round-to-byte, row-sum add.
-ALU_SLOTS_PER_PAIR = 7 + 4
+# Algorithmic vector-ALU work per (query, key) pair of the fused kernel, in issue
+# slots of a 16-lane SIMD ("lane-instructions"): bias unpack, scale, logit + bias,
+# running max, exponent FMA, round-to-byte, row-sum add (7 full-rate instructions)
+# plus one exponential.  v_exp_f32 issues at half rate on this chip (measured with
+# a dependent-free instruction stream: 2 slots), hence 7 + 2.
+ALU_SLOTS_PER_PAIR = 7 + 2
+# The same list with what the kernel's design makes unnecessary taken out (the FP4
+# matrix-core logits arrive in fp32 with the bias already added; v_max3 takes two
+# values per instruction; the sign offset of the byte codes costs a quarter
+# instruction): unpack 1, scale 1, max 0.5, FMA 1, exp 2, add 1, round 1, xor 0.25.
+ALU_SLOTS_PER_PAIR_STRICT = 7.75
 ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # 39.32
 MFMA_I8_PEAK_TOPS = 5033.0
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the fused kernel from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+# (two runs of this file; KiB per dispatch, scaled by what the same counters read for a
+# 512 MiB device-to-device copy: x2.0 and x1.0).  Summaries under profiles/.
+FUSED_TRAFFIC_BYTES = {"vit_hires": 8.93e9 + 0.07e9}
 
 
 def parse():
@@ -104,8 +114,9 @@ def run_workload(name, steps, warmup, with_bias=True):
         "mfma_tops_algorithmic": 4 * pairs * d / (fused_ms * 1e-3) / 1e12,
         # fused-kernel algorithmic HBM bytes: bias once per head (batch-shared), sign words,
         # K operand + V codes once per head, output
-        "fused_hbm_gbs": (2 * H * N * N + B * H * N * (W * 4 + 2 * 32 * W + 2 * d)) / (fused_ms * 1e-3) / 1e9,
+        "fused_hbm_bytes": 2 * H * N * N + B * H * N * (W * 4 + 2 * 32 * W + 2 * d),
     }
+    res["fused_hbm_gbs"] = res["fused_hbm_bytes"] / (fused_ms * 1e-3) / 1e9
     return res, x
 
 
@@ -169,9 +180,13 @@ def main():
         "fused_kernel_tops_equiv": res["fused_tops_equiv"],
         "pack_kernel_gbs": res["pack_gbs"],
         "roofline": {"bound": "alu", "achieved": res["alu_tlaneops"], "peak": ALU_PEAK_TLANEOPS,
-                     "unit": "T lane-instr/s", "frac": res["alu_tlaneops"] / ALU_PEAK_TLANEOPS, "traffic": None,
-                     "kernel": "fused_kernel (binattn_attend)",
-                     "algorithmic_lane_instr_per_pair": ALU_SLOTS_PER_PAIR},
+                     "unit": "T lane-instr/s", "frac": res["alu_tlaneops"] / ALU_PEAK_TLANEOPS,
+                     "traffic": None if a.no_bias else FUSED_TRAFFIC_BYTES.get(a.workload),
+                     "kernel": "fused_kernel (binattn_attend)", "kernel_ms": res["fused_ms"],
+                     "algorithmic_lane_instr_per_pair": ALU_SLOTS_PER_PAIR,
+                     "frac_strict_count": res["alu_tlaneops"] / ALU_PEAK_TLANEOPS
+                                          * ALU_SLOTS_PER_PAIR_STRICT / ALU_SLOTS_PER_PAIR,
+                     "algorithmic_hbm_bytes": res["fused_hbm_bytes"]},
         "roofline_other_bounds": {
             "mfma_int8_frac": res["mfma_tops_algorithmic"] / MFMA_I8_PEAK_TOPS,
             "hbm_frac": res["fused_hbm_gbs"] / HBM_PEAK_GBS, "hbm_gbs": res["fused_hbm_gbs"]},
@@ -187,10 +202,9 @@ def main():
             r["alu_frac"] = r["alu_tlaneops"] / ALU_PEAK_TLANEOPS
             others.append(r)
         line["other_workloads"] = others
-        if a.workload != wl.WORKLOAD_ORDER[-1]:
-            del x
-            torch.cuda.empty_cache()
-            _, x = run_workload(a.workload, 1, 0)
+        del x
+        torch.cuda.empty_cache()
+        _, x = run_workload(a.workload, 1, 0)   # the headline inputs again, for the CPU leg
     if a.no_bias:
         line["config"]["workload"] += " -- WITHOUT bias (diagnostic run)"
     if not a.no_cpu_baseline and not a.no_bias:

@@ -316,6 +316,42 @@ def test_masked_rows_via_minus_inf_bias_do_not_poison():
     check_close(got, ref, "masked: out vs O2")
 
 
+@pytest.mark.parametrize("kind", ["plain", "strong", "minus_inf_scattered", "minus_inf_blocks", "negative_scale"])
+def test_long_sequence_paired_kernel(kind):
+    # Even batch, batch-shared bf16 bias, >= 8 key blocks, d <= 64: the kernel that pairs batch
+    # entries and forms b / alpha on the matrix cores.  Non-finite bias values must fall back
+    # to the exact per-element form without touching their neighbours; 1160 = 9 * 128 + 8 keys
+    # leaves a ragged last block.
+    B, H, N, d = 2, 2, 1160, 64
+    say(f"paired long-sequence kernel: {kind}")
+    x = small_inputs(B, H, N, d, 300)
+    g = torch.Generator().manual_seed(11)
+    bias = x.bias
+    if kind == "strong":
+        bias = (torch.randn(H, N, N, generator=g) * 3.0).to(torch.bfloat16)
+    elif kind == "minus_inf_scattered":
+        bias = (torch.randn(H, N, N, generator=g) * 0.3)
+        bias[torch.rand(H, N, N, generator=g) < 0.01] = float("-inf")
+        bias[0, 5, :] = float("-inf")          # a row with a single visible key
+        bias[0, 5, 777] = 0.25
+        bias = bias.to(torch.bfloat16)
+    elif kind == "minus_inf_blocks":
+        bias = (torch.randn(H, N, N, generator=g) * 0.3)
+        bias[:, :, :300] = float("-inf")       # leading key blocks fully masked
+        bias[1, 200:400, 900:1160] = float("-inf")
+        bias = bias.to(torch.bfloat16)
+    elif kind == "negative_scale":
+        x.scale = -x.scale
+    got = run_forward(x, bias)
+    assert np.isfinite(got).all()
+    ref = oracle_algorithm1(x, bias, Bv=128)
+    err = np.abs(got - ref)
+    say(f"    vs Alg.1(Bv=128): max abs err {err.max():.3e}")
+    assert np.all(err <= 2e-3 + 2 ** -7 * np.abs(ref))
+    if kind in ("plain", "negative_scale"):
+        check_close(got, oracle_forward(x, bias)["O2"], "out vs O2")
+
+
 # ---- the five workloads ----------------------------------------------------------
 def test_workload_deit_tiny_full():
     w = wl.WORKLOADS["deit_tiny"]
