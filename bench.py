@@ -45,7 +45,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the fused kernel from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # (two runs of this file; KiB per dispatch, scaled by what the same counters read for a
 # 512 MiB device-to-device copy: x2.0 and x1.0).  Summaries under profiles/.
-FUSED_TRAFFIC_BYTES = {"vit_hires": 8.93e9 + 0.07e9}
+FUSED_TRAFFIC_BYTES = {"vit_hires": 8.83e9 + 0.07e9}
 
 
 def parse():

@@ -319,9 +319,9 @@ def test_masked_rows_via_minus_inf_bias_do_not_poison():
 @pytest.mark.parametrize("kind", ["plain", "strong", "minus_inf_scattered", "minus_inf_blocks", "negative_scale"])
 def test_long_sequence_paired_kernel(kind):
     # Even batch, batch-shared bf16 bias, >= 8 key blocks, d <= 64: the kernel that pairs batch
-    # entries and forms b / alpha on the matrix cores.  Non-finite bias values must fall back
-    # to the exact per-element form without touching their neighbours; 1160 = 9 * 128 + 8 keys
-    # leaves a ragged last block.
+    # entries in one workgroup and shares double-buffered bias tiles between them.  Masks
+    # (-inf bias values, scattered and as whole blocks) must not touch their neighbours;
+    # 1160 = 9 * 128 + 8 keys leaves a ragged last block.
     B, H, N, d = 2, 2, 1160, 64
     say(f"paired long-sequence kernel: {kind}")
     x = small_inputs(B, H, N, d, 300)
