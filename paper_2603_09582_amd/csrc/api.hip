@@ -123,7 +123,8 @@ int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
             // LDS staging needs 16-byte aligned rows made of whole 16-byte chunks, and LDS
             // room for two workgroups per CU (d <= 96); everything else takes register loads.
             const bool rows16 = aligned(bias, 16) && bs.b % 8 == 0 && bs.h % 8 == 0 && bs.n % 8 == 0;
-            mode = (rows16 && N % 8 == 0 && s.DK <= 3) ? BIAS_BF16_LDS : BIAS_BF16_VEC;
+            // (and a row pitch whose 7-fold fits a 32-bit lane offset)
+            mode = (rows16 && N % 8 == 0 && s.DK <= 3 && bs.n < (1 << 27)) ? BIAS_BF16_LDS : BIAS_BF16_VEC;
         } else {
             mode = BIAS_F32_VEC;
         }

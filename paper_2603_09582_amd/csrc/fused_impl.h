@@ -140,11 +140,18 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     // A wave copies RGW of the four 8-row groups of its 32-row tile: all four when the
     // tile is its own (NB = 1), two when the tile is shared with the other batch entry.
     constexpr int RGW = 4 / NB;
-    const char *bsrc[RGW];
+    // The copy address is a wave-uniform base (first row of the group, scalar registers,
+    // advanced by scalar arithmetic) plus a 32-bit lane offset that is fixed for an item.
+    struct BiasSrc {
+        const char *base[RGW];
+        unsigned voff[RGW];
+    };
+    BiasSrc bsrc;
     int dma_c[RGW];  // key chunk this lane fetches, per row group
 #pragma unroll
     for (int j = 0; j < RGW; ++j) {
-        bsrc[j] = nullptr;
+        bsrc.base[j] = nullptr;
+        bsrc.voff[j] = 0;
         dma_c[j] = (lane & 7) ^ (lane >> 3) ^ ((RGW * bsel + j) & 1);
     }
     float m_run, l_run, rho;  // running max (units of T = S / alpha), sum of 255 exp(S - m), rescale sum
@@ -167,12 +174,19 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         return static_cast<const char *>(p.bias) +
                ((int64_t)t.b * p.bs.b + (int64_t)t.h * p.bs.h + (int64_t)qc * p.bs.n) * bsb;
     };
-    auto bias_dma_ptr = [&](const Item &t, int j) -> const char * {
-        const int rg = RGW * bsel + j;
-        const int r = (lane >> 3) ^ (rg & 1);
-        const int row = min(t.rb * BR + wave * ROWS_PER_WAVE + 8 * rg + r, N - 1);
-        return static_cast<const char *>(p.bias) +
-               ((int64_t)t.b * p.bs.b + (int64_t)t.h * p.bs.h + (int64_t)row * p.bs.n) * 2 + 16 * dma_c[j];
+    auto bias_dma_src = [&](const Item &t) -> BiasSrc {
+        BiasSrc o;
+#pragma unroll
+        for (int j = 0; j < RGW; ++j) {
+            const int rg = RGW * bsel + j;
+            const int r = (lane >> 3) ^ (rg & 1);
+            const int row0 = min(t.rb * BR + wave * ROWS_PER_WAVE + 8 * rg, N - 1);  // uniform
+            const int row = min(row0 + r, N - 1);
+            o.base[j] = static_cast<const char *>(p.bias) +
+                        ((int64_t)t.b * p.bs.b + (int64_t)t.h * p.bs.h + (int64_t)row0 * p.bs.n) * 2;
+            o.voff[j] = (unsigned)(row - row0) * (unsigned)p.bs.n * 2u + 16u * dma_c[j];
+        }
+        return o;
     };
     auto image_ptr = [&](const Item &t) -> const char * {
         return p.img + (int64_t)t.bh * p.nblk * L::BYTES;
@@ -192,8 +206,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         load_q_operand<DK2>(pend_q, d, g, a_neg, a_zero, qB);
         if (MODE == BIAS_BF16_VEC || MODE == BIAS_F32_VEC) brow = bias_row_ptr(t);
         if (LDS_BIAS) {
-#pragma unroll
-            for (int j = 0; j < RGW; ++j) bsrc[j] = bias_dma_ptr(t, j);
+            bsrc = bias_dma_src(t);
         }
         m_run = -INFINITY;
         l_run = 0.0f;
@@ -205,14 +218,15 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     };
 
     // ---- bias access ----------------------------------------------------------
-    auto dma_bias = [&](const char *const src[RGW], int blk, unsigned region) {  // region: LDS offset of the 8 KiB tile
+    auto dma_bias = [&](const BiasSrc &src, int blk, unsigned region) {  // region: LDS offset of the 8 KiB tile
 #pragma unroll
         for (int j = 0; j < RGW; ++j)
 #pragma unroll
             for (int gh = 0; gh < 2; ++gh) {
                 const int key0 = blk * BV + 64 * gh + 8 * dma_c[j];
                 if (key0 + 8 <= N)
-                    dma16(src[j] + (blk * BV + 64 * gh) * 2, region + ((RGW * bsel + j) * 2 + gh) * 1024);
+                    dma16(src.base[j] + (blk * BV + 64 * gh) * 2, src.voff[j],
+                          region + ((RGW * bsel + j) * 2 + gh) * 1024);
             }
     };
     u4v braw[8];  // the 64 bf16 bias values of this lane for the current block
@@ -322,13 +336,11 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         const bool sw = PERSIST && last;  // ... which belongs to the next item
         const char *nimg = sw ? image_ptr(nxt) : imgs + (int64_t)(it + 1) * L::BYTES;
         const int nblkidx = sw ? 0 : it + 1;
-        const char *nsrc[RGW];
-#pragma unroll
-        for (int j = 0; j < RGW; ++j) nsrc[j] = (LDS_BIAS && sw) ? bias_dma_ptr(nxt, j) : bsrc[j];
+        const BiasSrc nsrc = (LDS_BIAS && sw) ? bias_dma_src(nxt) : bsrc;
         if (more) dma_image<DK>(nimg, inxt + bsel * L::BYTES, wave, lane);
         if (BIAS_DB && more) dma_bias(nsrc, nblkidx, bnxt);
         if (it == 0 && wave == 0 && lane < DKP / 4)  // delta_v of this item, for its epilogue
-            dma16(p.delta + (int64_t)cur.bh * DKP + 4 * lane, lds_offset(&sdelta[parity][bsel][0]));
+            dma16(p.delta + (int64_t)cur.bh * DKP, 16 * lane, lds_offset(&sdelta[parity][bsel][0]));
         if (sw && nxt.valid) fetch_item_regs(nxt);
 
         // 1. all LDS reads of the logit phase go out together: bias tile, key rows
