@@ -85,24 +85,61 @@ __device__ __forceinline__ float block_sum(float v, float *wsum) {
     return t;
 }
 
-// Long sequences: one workgroup per (tensor, head, token tile); mu through one
-// float atomic per workgroup into a zeroed buffer.
+// Long sequences: streaming form without LDS staging.  A lane owns one 16-byte chunk
+// (8 channels) of a token; a token takes 4 W consecutive lanes (slots past d stay idle), so
+// the four chunks of one 32-channel word sit in one lane quad and the word is assembled
+// with three quad broadcasts.  A workgroup streams PACK_STREAM_TOKENS tokens of one
+// (tensor, head), four loads in flight per lane; mu through one float atomic per workgroup
+// into a zeroed buffer.
+constexpr int PACK_STREAM_TOKENS = 512;
+
+template <int K>
+__device__ __forceinline__ unsigned quad_bcast(unsigned x) {  // value of lane K of this lane's quad
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, K * 0x55, 0xf, 0xf, true);
+}
+
 template <int C16>
-__global__ __launch_bounds__(PACK_THREADS) void pack_tile_kernel(PackSide q, PackSide k, int BH,
-                                                                 int H, int N, int ntile,
-                                                                 float inv_count) {
+__global__ __launch_bounds__(PACK_THREADS) void pack_stream_kernel(PackSide q, PackSide k, int BH,
+                                                                   int H, int N, int nseg,
+                                                                   float inv_count) {
     constexpr int W = (C16 + 3) / 4;
-    __shared__ uint32_t words[PACK_TOKENS * W];
+    constexpr int SLOTS = 4 * W;      // lanes per token
+    constexpr int TPW = 64 / SLOTS;   // tokens per wave and load
+    constexpr int U = 4;              // loads in flight per lane
     __shared__ float wsum[PACK_THREADS / 64];
-    const int side = blockIdx.x / (BH * ntile);
-    const int rem = blockIdx.x % (BH * ntile);
+    const int side = blockIdx.x / (BH * nseg);
+    const int rem = blockIdx.x % (BH * nseg);
     const PackSide &S = side ? k : q;
-    const int bh = rem / ntile, n0 = (rem % ntile) * PACK_TOKENS;
+    const int bh = rem / nseg, t0 = (rem % nseg) * PACK_STREAM_TOKENS;
+    const int tend = min(N, t0 + PACK_STREAM_TOKENS);
     const int b = bh / H, h = bh % H;
     const uint16_t *xb = S.x + (int64_t)b * S.xs.b + (int64_t)h * S.xs.h;
-    const float a = pack_tile<C16>(xb, S.xs.n, n0, min(PACK_TOKENS, N - n0),
-                                   S.bits + ((int64_t)bh * N + n0) * W, words);
-    const float t = block_sum(a, wsum);
+    uint32_t *ob = S.bits + (int64_t)bh * N * W;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tl = lane / SLOTS, slot = lane % SLOTS;
+    const bool lane_on = tl < TPW && slot < C16;
+    float asum = 0.0f;
+    for (int base = t0 + wave * TPW; base < tend; base += U * 4 * TPW) {
+        u4p v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int tok = base + u * 4 * TPW + tl;
+            v[u] = u4p{0x80008000u, 0x80008000u, 0x80008000u, 0x80008000u};  // -0.0: |x| = 0; bits masked below
+            if (lane_on && tok < tend)
+                v[u] = *reinterpret_cast<const u4p *>(xb + (int64_t)tok * S.xs.n + 8 * slot);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int tok = base + u * 4 * TPW + tl;
+            const bool on = lane_on && tok < tend;
+            unsigned bits = sign_bits8(make_uint4(v[u][0], v[u][1], v[u][2], v[u][3]), asum);
+            bits = on ? bits : 0u;  // padding bits are 0
+            const unsigned word = quad_bcast<0>(bits) | (quad_bcast<1>(bits) << 8) |
+                                  (quad_bcast<2>(bits) << 16) | (quad_bcast<3>(bits) << 24);
+            if ((slot & 3) == 0 && tl < TPW && tok < tend) ob[(int64_t)tok * W + (slot >> 2)] = word;
+        }
+    }
+    const float t = block_sum(asum, wsum);
     if (threadIdx.x == 0) atomicAdd(S.mu + bh, t * inv_count);
 }
 
@@ -146,9 +183,9 @@ static int launch_pack_t(const PackSide &q, const PackSide &k, const Shape &s, h
     }
     int rc = launch_zero_f32(q.mu, k.mu, s.BH, stream);
     if (rc != BINATTN_OK) return rc;
-    const int ntile = (s.N + PACK_TOKENS - 1) / PACK_TOKENS;
-    hipLaunchKernelGGL(pack_tile_kernel<C16>, dim3(2u * s.BH * ntile), dim3(PACK_THREADS), 0, stream,
-                       q, k, s.BH, s.H, s.N, ntile, inv);
+    const int nseg = (s.N + PACK_STREAM_TOKENS - 1) / PACK_STREAM_TOKENS;
+    hipLaunchKernelGGL(pack_stream_kernel<C16>, dim3(2u * s.BH * nseg), dim3(PACK_THREADS), 0, stream,
+                       q, k, s.BH, s.H, s.N, nseg, inv);
     return check_launch();
 }
 

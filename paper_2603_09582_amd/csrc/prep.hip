@@ -139,13 +139,15 @@ __device__ __forceinline__ void quant_v_block(const uint16_t *__restrict__ vb, i
         reinterpret_cast<uint32_t *>(tile)[i] = 0u;
     __syncthreads();
 
-    // One thread per (8-channel chunk, 4 consecutive tokens): consecutive lanes take
-    // consecutive token quads, so the transposed 4-byte LDS writes fall into
-    // consecutive banks.
+    // One thread per (4 consecutive tokens, 8-channel chunk); consecutive lanes take
+    // consecutive chunks of the same tokens, so every load instruction reads whole token
+    // rows.  The transposed 4-byte LDS writes of a wave (8 token quads x 8 chunks at d = 64)
+    // would fall on 16 banks; XOR-ing bits of the chunk index into the quad's column spreads
+    // them over all 64 (the copy-out below undoes it at 16-byte granularity).
     const int j0 = blk * BV;
     const int nrow = min(BV, N - j0);
     for (int e = threadIdx.x; e < C16 * (BV / 4); e += PREP_THREADS) {
-        const int c = e / (BV / 4), jq = e % (BV / 4);
+        const int c = e % C16, jq = e / C16;
         unsigned packed[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) packed[i] = 0u;
@@ -167,15 +169,17 @@ __device__ __forceinline__ void quant_v_block(const uint16_t *__restrict__ vb, i
                 }
             }
         }
+        const int col = jq ^ (((c >> 1) & 3) << 3);
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            *reinterpret_cast<unsigned *>(tile + (8 * c + i) * LDT + 4 * jq) = packed[i];
+            *reinterpret_cast<unsigned *>(tile + (8 * c + i) * LDT + 4 * col) = packed[i];
     }
     __syncthreads();
 
     for (int i = threadIdx.x; i < DKP * (BV / 16); i += PREP_THREADS) {
         const int c = i / (BV / 16), part = i % (BV / 16);
-        const u4 val = *reinterpret_cast<const u4 *>(tile + c * LDT + 16 * part);
+        const int spart = part ^ (((c >> 4) & 3) << 1);  // where the writer put this token group
+        const u4 val = *reinterpret_cast<const u4 *>(tile + c * LDT + 16 * spart);
         *reinterpret_cast<u4 *>(dst + v_off + c * LDT + 16 * part) = val;
     }
     if (threadIdx.x < DKP) {
@@ -216,11 +220,32 @@ __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(
         const int W = (d + 31) / 32;
         expand_k_block(k_bits + (int64_t)bh * N * W, N, d, W, blk, KP, dst);
     }
+    // The head's absmax from the per-chunk partials: all threads load (independent,
+    // coalesced), the maximum is taken in LDS on the bit patterns (non-negative floats
+    // order like integers).
+    __shared__ int sabs[8 * C16];
+    if (threadIdx.x < 8 * C16) sabs[threadIdx.x] = 0;
+    __syncthreads();
+    {
+        const float *am = amax + (int64_t)bh * nchunk * DKP;
+        const int total = nchunk * DKP;
+        for (int i0 = threadIdx.x; i0 < total; i0 += 4 * PREP_THREADS) {
+            float a[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * PREP_THREADS;
+                a[u] = i < total ? am[i] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = (i0 + u * PREP_THREADS) % DKP;
+                if (c < 8 * C16 && a[u] > 0.0f) atomicMax(&sabs[c], __float_as_int(a[u]));
+            }
+        }
+    }
+    __syncthreads();
     if (threadIdx.x < 8 * C16) {
-        float a = 0.0f;
-        for (int i = 0; i < nchunk; ++i)
-            a = fmaxf(a, amax[((int64_t)bh * nchunk + i) * DKP + threadIdx.x]);
-        const float dl = delta_of_absmax(a);
+        const float dl = delta_of_absmax(__int_as_float(sabs[threadIdx.x]));
         sdelta[threadIdx.x] = dl;
         srcp[threadIdx.x] = __fdiv_rn(1.0f, dl);
         if (blk == 0) delta[(int64_t)bh * DKP + threadIdx.x] = dl;

@@ -65,6 +65,21 @@ def test_pack_bits_exact_and_mu(B, H, N, d):
                 assert float(mu[b, h]) == pytest.approx(orc.abs_mean(np_bits(t[b, h])), rel=2e-6)
 
 
+@pytest.mark.parametrize("B,H,N,d", [(1, 2, 2100, 72), (2, 1, 2049, 8), (1, 1, 2560, 128), (1, 3, 3001, 40),
+                                     (1, 1, 4096, 64), (1, 1, 2300, 104)])
+def test_pack_long_sequences_streaming_kernel(B, H, N, d):
+    # N > 2048 takes the streaming pack kernel (lane quads assemble the words, mu by atomics)
+    say(f"pack (long) B={B} H={H} N={N} d={d}")
+    x = small_inputs(B, H, N, d, 900 + d)
+    qb, kb, mq, mk = ba.pack_qk(dev(x.q), dev(x.k))
+    torch.cuda.synchronize()
+    for t, bits, mu in ((x.q, qb, mq), (x.k, kb, mk)):
+        assert np.array_equal(bits.cpu().numpy().view(np.uint32), orc.sign_pack(np_bits(t)))
+        for b in range(B):
+            for h in range(H):
+                assert float(mu[b, h]) == pytest.approx(orc.abs_mean(np_bits(t[b, h])), rel=2e-6)
+
+
 def test_pack_special_values_and_strided_input():
     say("pack special values / strides")
     N, d = 40, 72
