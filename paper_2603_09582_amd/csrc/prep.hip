@@ -70,6 +70,21 @@ __device__ __forceinline__ void unpack8(u4 w, float f[8]) {
     }
 }
 
+// Running absmax of 8 bf16 values per lane on their bit patterns: with the sign bit
+// cleared, bf16 magnitudes order like 16-bit unsigned integers (two values per instruction).
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void absmax_acc(unsigned m[4], u4 w) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const us2 a = __builtin_bit_cast(us2, m[i]);
+        const us2 b = __builtin_bit_cast(us2, w[i] & 0x7FFF7FFFu);
+        m[i] = __builtin_bit_cast(unsigned, __builtin_elementwise_max(a, b));
+    }
+}
+__device__ __forceinline__ void absmax_floats(const unsigned m[4], float f[8]) {
+    unpack8(u4{m[0], m[1], m[2], m[3]}, f);
+}
+
 // absmax over token rows [n0, n1) of one head, all threads of the workgroup:
 // on return thread c < 8 * C16 holds max_n |v[n][c]| (other threads 0).
 // smax: LDS scratch of (PREP_THREADS / C16) * 8 * C16 floats.
@@ -80,9 +95,7 @@ __device__ __forceinline__ float absmax_rows(const uint16_t *__restrict__ vb, in
     constexpr int D = 8 * C16;
     const int c = threadIdx.x % C16, r0 = threadIdx.x / C16;
     if (r0 < RT) {
-        float m[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) m[i] = 0.0f;
+        unsigned mb[4] = {0u, 0u, 0u, 0u};
         // four rows per trip, their loads issued together (the loop is latency-bound)
         const u4 zero4 = {0u, 0u, 0u, 0u};
         for (int n = n0 + r0; n < n1; n += 4 * RT) {
@@ -93,13 +106,10 @@ __device__ __forceinline__ float absmax_rows(const uint16_t *__restrict__ vb, in
                            ? *reinterpret_cast<const u4 *>(vb + (int64_t)(n + k * RT) * stride_n + 8 * c)
                            : zero4;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                float f[8];
-                unpack8(w[k], f);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) m[i] = fmaxf(m[i], fabsf(f[i]));
-            }
+            for (int k = 0; k < 4; ++k) absmax_acc(mb, w[k]);
         }
+        float m[8];
+        absmax_floats(mb, m);
 #pragma unroll
         for (int i = 0; i < 8; ++i) smax[r0 * D + 8 * c + i] = m[i];
     }
@@ -116,14 +126,47 @@ __device__ __forceinline__ float delta_of_absmax(float a) {
 }
 
 // Eq. 7: code = round-to-nearest-even(v / delta), clamped to [-127, 127], where the
-// quotient is the IEEE fp32 one.  v * (1 / delta) is within 2.3e-5 of that quotient
-// (|v / delta| <= 127), so its rounding is already decided unless it sits that close
-// to a half-integer; only then (or if 1 / delta overflowed) is the exact division needed.
-__device__ __forceinline__ float quant_code(float v, float delta, float rcp_delta) {
-    const float t = v * rcp_delta;
-    float q = rintf(t);
-    if (!(fabsf(t) < 200.0f) || fabsf(fabsf(t - q) - 0.5f) < 1e-4f) q = rintf(__fdiv_rn(v, delta));
-    return fminf(fmaxf(q, -127.0f), 127.0f);
+// quotient is the IEEE fp32 one.  t = v * (1 / delta) is within 2.3e-5 of that quotient
+// (|v / delta| <= 127), so its rounding is already decided unless t sits that close to a
+// half-integer; only then is the exact division needed.  Clamping t first is equivalent
+// (the bounds are integers).  Rounding is the fp32 addition of 1.5 * 2^23, whose result
+// carries the two's complement code in its low byte.  thr = 0.4999 normally; a channel whose
+// 1 / delta is not finite passes thr < 0 and rcp = 0, which sends every element to the division.
+constexpr float QMAGIC = 12582912.0f;  // 1.5 * 2^23
+__device__ __forceinline__ unsigned quant_bits(float v, float delta, float rcp_delta, float thr) {
+    const float t = __builtin_amdgcn_fmed3f(v * rcp_delta, -127.0f, 127.0f);
+    float s = t + QMAGIC;
+    const float q = s - QMAGIC;
+    if (fabsf(t - q) > thr) {
+        const float e = fminf(fmaxf(rintf(__fdiv_rn(v, delta)), -127.0f), 127.0f);
+        s = e + QMAGIC;
+    }
+    return __float_as_uint(s);
+}
+// codes of 4 tokens x 8 channels (w[k]: token k), one dword per channel, token k in byte k
+__device__ __forceinline__ void quant_quad(const u4 w[4], const float *sdelta, const float *srcp,
+                                           const float *sthr, int c, unsigned packed[8]) {
+    float f[4][8];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) unpack8(w[k], f[k]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float dl = sdelta[8 * c + i], rc = srcp[8 * c + i], th = sthr[8 * c + i];
+        unsigned b[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) b[k] = quant_bits(f[k][i], dl, rc, th);
+        const unsigned lo = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
+        const unsigned hi = __builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u);
+        packed[i] = lo | (hi << 16);
+    }
+}
+// per-channel constants of the quantiser from the channel's absmax
+__device__ __forceinline__ void quant_consts(float a, float *dl, float *rc, float *th) {
+    *dl = delta_of_absmax(a);
+    const float r = __fdiv_rn(1.0f, *dl);
+    const bool ok = r < 3.0e38f;
+    *rc = ok ? r : 0.0f;
+    *th = ok ? 0.4999f : -1.0f;
 }
 
 // Key block `blk` of one head: codes (channel-major) and the accumulator seeds
@@ -132,8 +175,8 @@ __device__ __forceinline__ float quant_code(float v, float delta, float rcp_delt
 template <int C16>
 __device__ __forceinline__ void quant_v_block(const uint16_t *__restrict__ vb, int64_t stride_n,
                                               int N, int DKP, int blk, const float *sdelta,
-                                              const float *srcp, int8_t *tile, int v_off,
-                                              int cs_off, char *__restrict__ dst) {
+                                              const float *srcp, const float *sthr, int8_t *tile,
+                                              int v_off, int cs_off, char *__restrict__ dst) {
     constexpr int LDT = BV + 16;  // LDS row pitch in bytes = Image::VP
     for (int i = threadIdx.x; i < DKP * LDT / 4; i += PREP_THREADS)
         reinterpret_cast<uint32_t *>(tile)[i] = 0u;
@@ -149,26 +192,14 @@ __device__ __forceinline__ void quant_v_block(const uint16_t *__restrict__ vb, i
     for (int e = threadIdx.x; e < C16 * (BV / 4); e += PREP_THREADS) {
         const int c = e % C16, jq = e / C16;
         unsigned packed[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) packed[i] = 0u;
         u4 w[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int jl = min(4 * jq + k, nrow - 1);  // clamped; rows beyond nrow are dropped below
-            w[k] = *reinterpret_cast<const u4 *>(vb + (int64_t)(j0 + jl) * stride_n + 8 * c);
+        for (int k = 0; k < 4; ++k) {  // rows beyond the block's end read as zeros: code 0
+            w[k] = u4{0u, 0u, 0u, 0u};
+            if (4 * jq + k < nrow)
+                w[k] = *reinterpret_cast<const u4 *>(vb + (int64_t)(j0 + 4 * jq + k) * stride_n + 8 * c);
         }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            if (4 * jq + k < nrow) {
-                float f[8];
-                unpack8(w[k], f);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float q = quant_code(f[i], sdelta[8 * c + i], srcp[8 * c + i]);
-                    packed[i] |= ((unsigned)(int)q & 0xFFu) << (8 * k);
-                }
-            }
-        }
+        quant_quad(w, sdelta, srcp, sthr, c, packed);
         const int col = jq ^ (((c >> 1) & 3) << 3);
 #pragma unroll
         for (int i = 0; i < 8; ++i)
@@ -182,9 +213,14 @@ __device__ __forceinline__ void quant_v_block(const uint16_t *__restrict__ vb, i
         const u4 val = *reinterpret_cast<const u4 *>(tile + c * LDT + 16 * spart);
         *reinterpret_cast<u4 *>(dst + v_off + c * LDT + 16 * part) = val;
     }
-    if (threadIdx.x < DKP) {
+    if (threadIdx.x < DKP) {  // column sums: 16 bytes per read, four signed bytes per dot
         int sum = 0;
-        for (int j = 0; j < BV; ++j) sum += (int)tile[threadIdx.x * LDT + j];
+#pragma unroll
+        for (int j = 0; j < BV / 16; ++j) {
+            const u4 w = *reinterpret_cast<const u4 *>(tile + threadIdx.x * LDT + 16 * j);
+#pragma unroll
+            for (int n = 0; n < 4; ++n) sum = __builtin_amdgcn_sdot4((int)w[n], 0x01010101, sum, false);
+        }
         reinterpret_cast<int *>(dst + cs_off)[threadIdx.x] = PV_MAGIC_BITS + 128 * sum;
     }
 }
@@ -210,7 +246,7 @@ __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(
     const uint16_t *__restrict__ v, Strides3 vs, const uint32_t *__restrict__ k_bits, int H, int N,
     int d, int DKP, int nchunk, int nblk, const float *__restrict__ amax, float *__restrict__ delta,
     int img_bytes, int KP, int v_off, int cs_off, char *__restrict__ img) {
-    __shared__ float sdelta[8 * C16], srcp[8 * C16];
+    __shared__ float sdelta[8 * C16], srcp[8 * C16], sthr[8 * C16];
     __shared__ __attribute__((aligned(16))) int8_t tile[128 * (BV + 16)];
     const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
     const int b = bh / H, h = bh % H;
@@ -245,40 +281,110 @@ __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(
     }
     __syncthreads();
     if (threadIdx.x < 8 * C16) {
-        const float dl = delta_of_absmax(__int_as_float(sabs[threadIdx.x]));
+        float dl;
+        quant_consts(__int_as_float(sabs[threadIdx.x]), &dl, &srcp[threadIdx.x], &sthr[threadIdx.x]);
         sdelta[threadIdx.x] = dl;
-        srcp[threadIdx.x] = __fdiv_rn(1.0f, dl);
         if (blk == 0) delta[(int64_t)bh * DKP + threadIdx.x] = dl;
     }
-    quant_v_block<C16>(vb, vs.n, N, DKP, blk, sdelta, srcp, tile, v_off, cs_off, dst);
+    quant_v_block<C16>(vb, vs.n, N, DKP, blk, sdelta, srcp, sthr, tile, v_off, cs_off, dst);
 }
 
-// Short sequences: everything for one key block of one head in ONE launch.  Every
-// workgroup recomputes the head's absmax itself (N * d elements, cheap while N is
-// small and served by L2 after the first reader), so there is no dependency
-// between workgroups and no second or third launch.
+// Short sequences (at most two key blocks): everything for one head in ONE launch and ONE
+// pass over V.  All of the head's V rows go into registers first (a thread owns quads of
+// consecutive tokens of one 8-channel chunk; consecutive lanes take consecutive chunks, so a
+// load instruction reads whole token rows), the absmax is reduced through LDS, and the codes
+// are made from the same registers; nothing is read twice and only one load latency is paid.
 template <int C16>
-__global__ __launch_bounds__(PREP_THREADS) void prep_block_kernel(
+__global__ __launch_bounds__(PREP_THREADS) void prep_head_kernel(
     const uint16_t *__restrict__ v, Strides3 vs, const uint32_t *__restrict__ k_bits, int H, int N,
     int d, int DKP, int nblk, float *__restrict__ delta, int img_bytes, int KP, int v_off, int cs_off,
     char *__restrict__ img) {
-    __shared__ float smax[(PREP_THREADS / C16) * 8 * C16];
-    __shared__ float sdelta[8 * C16], srcp[8 * C16];
-    __shared__ __attribute__((aligned(16))) int8_t tile[128 * (BV + 16)];
-    const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
-    const int b = bh / H, h = bh % H;
+    constexpr int RT = PREP_THREADS / C16;  // thread groups = token quads per pass
+    constexpr int D = 8 * C16;
+    constexpr int NQ = 2 * BV / 4;          // token quads of two key blocks
+    constexpr int MAXQ = (NQ + RT - 1) / RT;
+    constexpr int LDT = BV + 16;            // = Image::VP
+    __shared__ float smax[RT * D];
+    __shared__ float sdelta[D], srcp[D], sthr[D];
+    __shared__ __attribute__((aligned(16))) int8_t tile[2 * 128 * LDT];
+    const int bh = blockIdx.x, b = bh / H, h = bh % H;
     const int W = (d + 31) / 32;
     const uint16_t *vb = v + (int64_t)b * vs.b + (int64_t)h * vs.h;
-    char *dst = img + ((int64_t)bh * nblk + blk) * img_bytes;
-    expand_k_block(k_bits + (int64_t)bh * N * W, N, d, W, blk, KP, dst);
-    const float a = absmax_rows<C16>(vb, vs.n, 0, N, smax);
-    if (threadIdx.x < 8 * C16) {
-        const float dl = delta_of_absmax(a);
-        sdelta[threadIdx.x] = dl;
-        srcp[threadIdx.x] = __fdiv_rn(1.0f, dl);
-        if (blk == 0) delta[(int64_t)bh * DKP + threadIdx.x] = dl;
+    char *dst = img + (int64_t)bh * nblk * img_bytes;
+    const int c = threadIdx.x % C16, r0 = threadIdx.x / C16;
+    const bool on = r0 < RT;
+
+    u4 w[MAXQ][4];
+#pragma unroll
+    for (int k = 0; k < MAXQ; ++k)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {  // rows beyond N read as zeros: no effect on a maximum, code 0
+            const int row = 4 * (r0 + k * RT) + t;
+            w[k][t] = u4{0u, 0u, 0u, 0u};
+            if (on && row < N) w[k][t] = *reinterpret_cast<const u4 *>(vb + (int64_t)row * vs.n + 8 * c);
+        }
+    for (int blk = 0; blk < nblk; ++blk)
+        expand_k_block(k_bits + (int64_t)bh * N * W, N, d, W, blk, KP, dst + (int64_t)blk * img_bytes);
+    for (int i = threadIdx.x; i < nblk * DKP * LDT / 4; i += PREP_THREADS)
+        reinterpret_cast<uint32_t *>(tile)[i] = 0u;
+
+    if (on) {
+        unsigned mb[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int k = 0; k < MAXQ; ++k)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) absmax_acc(mb, w[k][t]);
+        float m[8];
+        absmax_floats(mb, m);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) smax[r0 * D + 8 * c + i] = m[i];
     }
-    quant_v_block<C16>(vb, vs.n, N, DKP, blk, sdelta, srcp, tile, v_off, cs_off, dst);
+    __syncthreads();
+    if (threadIdx.x < D) {
+        float a = 0.0f;
+        for (int r = 0; r < RT; ++r) a = fmaxf(a, smax[r * D + threadIdx.x]);
+        float dl;
+        quant_consts(a, &dl, &srcp[threadIdx.x], &sthr[threadIdx.x]);
+        sdelta[threadIdx.x] = dl;
+        delta[(int64_t)bh * DKP + threadIdx.x] = dl;
+    }
+    __syncthreads();
+
+    if (on) {
+#pragma unroll
+        for (int k = 0; k < MAXQ; ++k) {
+            const int quad = r0 + k * RT;
+            if (4 * quad < N && quad < NQ) {
+                unsigned packed[8];
+                quant_quad(w[k], sdelta, srcp, sthr, c, packed);
+                const int blk = quad / (BV / 4), jq = quad % (BV / 4);
+                const int col = jq ^ (((c >> 1) & 3) << 3);  // see quant_v_block
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    *reinterpret_cast<unsigned *>(tile + (blk * DKP + 8 * c + i) * LDT + 4 * col) = packed[i];
+            }
+        }
+    }
+    __syncthreads();
+
+    for (int i = threadIdx.x; i < nblk * DKP * (BV / 16); i += PREP_THREADS) {
+        const int row = i / (BV / 16), part = i % (BV / 16);  // row = blk * DKP + channel
+        const int blk = row / DKP, ch = row % DKP;
+        const int spart = part ^ (((ch >> 4) & 3) << 1);
+        const u4 val = *reinterpret_cast<const u4 *>(tile + row * LDT + 16 * spart);
+        *reinterpret_cast<u4 *>(dst + (int64_t)blk * img_bytes + v_off + ch * LDT + 16 * part) = val;
+    }
+    if (threadIdx.x < nblk * DKP) {  // column sums: 16 bytes per read, four signed bytes per dot
+        const int blk = threadIdx.x / DKP, ch = threadIdx.x % DKP;
+        int sum = 0;
+#pragma unroll
+        for (int j = 0; j < BV / 16; ++j) {
+            const u4 x = *reinterpret_cast<const u4 *>(tile + threadIdx.x * LDT + 16 * j);
+#pragma unroll
+            for (int n = 0; n < 4; ++n) sum = __builtin_amdgcn_sdot4((int)x[n], 0x01010101, sum, false);
+        }
+        reinterpret_cast<int *>(dst + (int64_t)blk * img_bytes + cs_off)[ch] = PV_MAGIC_BITS + 128 * sum;
+    }
 }
 
 // Codes and delta from the private layout into [B,H,N,d] / [B,H,d].
@@ -312,8 +418,8 @@ int launch_expand_k(const uint32_t *k_bits, const Shape &s, char *ws, const Work
     return check_launch();
 }
 
-// Sequences up to this many key blocks take the single-launch path (every workgroup
-// recomputes the head's absmax); longer ones take absmax partials + one more launch.
+// Sequences up to this many key blocks take the single-launch path (one workgroup per
+// head); longer ones take absmax partials + one more launch.
 constexpr int PREP_FUSED_MAX_BLOCKS = 2;
 
 template <int C16>
@@ -325,9 +431,9 @@ static void launch_quant_v_t(const void *v, Strides3 vs, const uint32_t *k_bits,
     int KP, v_off, cs_off;
     image_offsets(s.DK, &KP, &v_off, &cs_off);
     if (k_bits != nullptr && s.nblk <= PREP_FUSED_MAX_BLOCKS) {
-        hipLaunchKernelGGL(prep_block_kernel<C16>, dim3((unsigned)s.nblk * s.BH), dim3(PREP_THREADS),
-                           0, stream, vp, vs, k_bits, s.H, s.N, s.d, s.DKP, s.nblk, delta,
-                           w.img_bytes, KP, v_off, cs_off, ws + w.img);
+        hipLaunchKernelGGL(prep_head_kernel<C16>, dim3((unsigned)s.BH), dim3(PREP_THREADS), 0, stream,
+                           vp, vs, k_bits, s.H, s.N, s.d, s.DKP, s.nblk, delta, w.img_bytes, KP,
+                           v_off, cs_off, ws + w.img);
         return;
     }
     hipLaunchKernelGGL(v_absmax_kernel<C16>, dim3((unsigned)s.nchunk * s.BH), dim3(PREP_THREADS),
