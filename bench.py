@@ -55,6 +55,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="vit_hires")
     ap.add_argument("--others", action="store_true", help="also time the other workloads (extra field)")
+    ap.add_argument("--sweep", choices=["hd128"], help="also time the head-dim-128 sequence-length sweep (extra field)")
+    ap.add_argument("--sweep-bias", action="store_true", help="run the sweep with a dense bias (up to N = 16384)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bias", action="store_true", help="run without the bias term (not the headline config)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -205,6 +207,22 @@ def main():
         del x
         torch.cuda.empty_cache()
         _, x = run_workload(a.workload, 1, 0)   # the headline inputs again, for the CPU leg
+    if a.sweep:
+        del x
+        torch.cuda.empty_cache()
+        rows = []
+        for name in wl.SWEEP_HD128:
+            w = wl.WORKLOADS[name]
+            if a.sweep_bias and w.N > 16384:
+                continue
+            r, xs = run_workload(name, max(5, a.steps), a.warmup, with_bias=a.sweep_bias)
+            del xs
+            torch.cuda.empty_cache()
+            r["bias"] = bool(a.sweep_bias)
+            rows.append({k: r[k] for k in ("workload", "B", "H", "N", "d", "bias", "ms_per_step", "pack_ms",
+                                           "prepare_ms", "fused_ms", "tops_equiv", "fused_tops_equiv")})
+        line["sweep_hd128"] = rows
+        _, x = run_workload(a.workload, 1, 0)
     if a.no_bias:
         line["config"]["workload"] += " -- WITHOUT bias (diagnostic run)"
     if not a.no_cpu_baseline and not a.no_bias:

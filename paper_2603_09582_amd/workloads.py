@@ -66,6 +66,14 @@ WORKLOADS = {
     "vit_hires": Workload("vit_hires", 2, 16, 16384, 64, 4, "token_outliers",
                           "high-resolution ViT, 128x128 patch grid"),
 }
+# Kernel-speed setting of Sec. 5.1's speed figure: head dimension 128 over a range of sequence
+# lengths.  The paper states neither batch nor head count; 16 heads and a batch that keeps
+# B * N = 16384 tokens are used here (the usual convention of attention kernel benchmarks).
+SWEEP_HD128 = [f"hd128_n{n}" for n in (1024, 2048, 4096, 8192, 16384, 32768)]
+for _i, _name in enumerate(SWEEP_HD128):
+    _n = int(_name.split("_n")[1])
+    WORKLOADS[_name] = Workload(_name, max(1, 16384 // _n), 16, _n, 128, 100 + _i, "",
+                                "head dim 128 sequence-length sweep")
 # Order of the benchmark's `configs` list.
 WORKLOAD_ORDER = ["deit_tiny", "deit_base", "dit_xl2_256", "dit_xl2_512", "vit_hires"]
 

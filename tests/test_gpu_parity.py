@@ -425,3 +425,13 @@ def test_workload_vit_hires_sampled_rows():
     rows = sorted(set(list(range(0, 32)) + list(range(8160, 8192)) + list(range(N - 32, N)) +
                       rng.integers(0, N, 64).tolist()))
     _sampled_check("vit_hires", [(0, 0), (1, 15)], rows)
+
+
+def test_sweep_hd128_sampled_rows():
+    # head dimension 128 (four channel blocks, register-path bias): the kernel-speed setting
+    name = "hd128_n4096"
+    N = wl.WORKLOADS[name].N
+    rng = np.random.default_rng(1)
+    rows = sorted(set(list(range(0, 16)) + list(range(N - 16, N)) + rng.integers(0, N, 32).tolist()))
+    _sampled_check(name, [(0, 0), (3, 15)], rows)
+
