@@ -435,3 +435,14 @@ def test_sweep_hd128_sampled_rows():
     rows = sorted(set(list(range(0, 16)) + list(range(N - 16, N)) + rng.integers(0, N, 32).tolist()))
     _sampled_check(name, [(0, 0), (3, 15)], rows)
 
+
+
+def test_against_stored_oracle_outputs():
+    # tests/golden/oracle_small.txt holds oracle outputs written by a committed script
+    from tests.test_oracle_pins import read_golden
+    for name, case in read_golden().items():
+        B, H, N, d, seed = case["shape"]
+        say(f"stored case {name}")
+        x = small_inputs(B, H, N, d, seed)
+        got = run_forward(x, x.bias)
+        check_close(got, case["O2"].reshape(B, H, N, d), f"{name}: out vs stored O2")

@@ -403,3 +403,37 @@ def test_forward_driver_composes_heads_and_shares_bias_over_batch():
     assert res["mu_q"][b, h] == orc.abs_mean(q[b, h])
     nomu = orc.forward(q, k, v, bias, 0.125, use_mu=False, heads=[(0, 0)])
     assert nomu["mu_q"][0, 0] == 1.0 and not np.allclose(nomu["O2"][0, 0], res["O2"][0, 0])
+
+
+# --------------------------------------------------------------------------
+# stored oracle outputs (tests/golden/oracle_small.txt, written by make_oracle_golden.py)
+# --------------------------------------------------------------------------
+def read_golden():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "oracle_small.txt")
+    cases, cur = {}, None
+    for line in open(path):
+        if line.startswith("#"):
+            continue
+        tok = line.split()
+        if tok[0] == "case":
+            cur = {"shape": tuple(int(t.split("=")[1]) for t in tok[2:7])}
+            cases[tok[1]] = cur
+        else:
+            vals = np.array([float(t) for t in tok[2:]], dtype=np.float64)
+            assert vals.size == int(tok[1])
+            cur[tok[0]] = vals
+    return cases
+
+
+def test_oracle_reproduces_stored_outputs():
+    from paper_2603_09582_amd import workloads as wl
+    for name, case in read_golden().items():
+        B, H, N, d, seed = case["shape"]
+        x = wl.make_inputs(wl.custom_workload(B, H, N, d, seed), device="cpu")
+        res = orc.forward(bf16_bits(x.q), bf16_bits(x.k), bf16_bits(x.v), bf16_bits(x.bias), x.scale,
+                          want=("O2", "O1"))
+        for key in ("mu_q", "mu_k", "O2", "O1"):
+            if key in case:
+                got = np.asarray(res[key], dtype=np.float64).reshape(-1)
+                assert np.allclose(got, case[key], rtol=1e-13, atol=1e-15), (name, key)
