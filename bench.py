@@ -55,6 +55,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="vit_hires")
     ap.add_argument("--others", action="store_true", help="also time the other workloads (extra field)")
+    ap.add_argument("--axial", action="store_true",
+                    help="also time the workload with the in-kernel decomposed relative-position bias (extra field)")
     ap.add_argument("--sweep", choices=["hd128"], help="also time the head-dim-128 sequence-length sweep (extra field)")
     ap.add_argument("--sweep-bias", action="store_true", help="run the sweep with a dense bias (up to N = 16384)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -63,13 +65,22 @@ def parse():
     return ap.parse_args()
 
 
-def run_workload(name, steps, warmup, with_bias=True):
+def axial_grid(N):
+    """Gy, Gx with Gy * Gx = N and Gx a power of two in [16, 256] (square when possible)."""
+    import math
+    gx = 1 << max(4, min(8, int(round(math.log2(max(N, 1)) / 2))))
+    while gx > 16 and N % gx:
+        gx //= 2
+    return (N // gx, gx) if N % gx == 0 and N // gx <= 256 else None
+
+
+def run_workload(name, steps, warmup, with_bias=True, axial=False):
     import torch
     from paper_2603_09582_amd import binding as ba
     from paper_2603_09582_amd import workloads as wl
 
     w = wl.WORKLOADS[name]
-    x = wl.make_inputs(w, device="cuda", with_bias=with_bias)
+    x = wl.make_inputs(w, device="cuda", with_bias=with_bias and not axial)
     B, H, N, d = w.B, w.H, w.N, w.d
     W = (d + 31) // 32
     dev = x.q.device
@@ -80,6 +91,12 @@ def run_workload(name, steps, warmup, with_bias=True):
     out = torch.empty(B, H, N, d, dtype=torch.bfloat16, device=dev)
     ws = ba.alloc_workspace(B, H, N, d, dev)
 
+    if axial:  # decomposed relative-position bias: two small tables per head instead of [H, N, N]
+        Gy, Gx = axial_grid(N)
+        gen = torch.Generator(device="cuda").manual_seed(w.seed + 1000)
+        by = torch.randn(H, 2 * Gy - 1, generator=gen, device=dev) * 0.02
+        bx = torch.randn(H, 2 * Gx - 1, generator=gen, device=dev) * 0.02
+
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
 
     def step(e=None):
@@ -88,7 +105,10 @@ def run_workload(name, steps, warmup, with_bias=True):
         if e: e[1].record()
         ba.prepare_kv(k_bits, x.v, ws)
         if e: e[2].record()
-        ba.attend(q_bits, mu_q, mu_k, x.bias, x.scale, d, ws, out=out)
+        if axial:
+            ba.attend_axial(q_bits, mu_q, mu_k, by, bx, x.scale, d, ws, out=out)
+        else:
+            ba.attend(q_bits, mu_q, mu_k, x.bias, x.scale, d, ws, out=out)
         if e: e[3].record()
 
     for _ in range(warmup):
@@ -207,6 +227,17 @@ def main():
         del x
         torch.cuda.empty_cache()
         _, x = run_workload(a.workload, 1, 0)   # the headline inputs again, for the CPU leg
+    if a.axial and axial_grid(wl.WORKLOADS[a.workload].N):
+        del x
+        torch.cuda.empty_cache()
+        r, xa = run_workload(a.workload, a.steps, a.warmup, axial=True)
+        del xa
+        torch.cuda.empty_cache()
+        Gy, Gx = axial_grid(r["N"])
+        line["axial_bias"] = {"grid": [Gy, Gx], "ms_per_step": r["ms_per_step"], "attend_ms": r["fused_ms"],
+                              "tops_equiv": r["tops_equiv"], "fused_kernel_tops_equiv": r["fused_tops_equiv"],
+                              "note": "b_ij = y[iy-jy] + x[ix-jx] from two fp32 tables per head held in LDS"}
+        _, x = run_workload(a.workload, 1, 0)
     if a.sweep:
         del x
         torch.cuda.empty_cache()

@@ -125,6 +125,23 @@ int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
                    size_t workspace_bytes, unsigned flags, void *stream);
 
 /*
+ * binattn_attend with a DECOMPOSED relative-position bias generated inside the kernel
+ * instead of a dense [N, N] matrix (Sec. 4.2: the bias "can be instantiated as
+ * position-sensitive"; Sec. 5.4 memory study: "a decomposable bias, e.g. a sum over spatial
+ * directions", whose memory overhead is negligible).  Tokens form a Gy x Gx grid in
+ * row-major order, n = iy * Gx + ix, with Gy * Gx = N, and
+ *     b_ij = bias_y[h][iy - jy + Gy - 1] + bias_x[h][ix - jx + Gx - 1].
+ *   bias_y : float32 [H, 2 Gy - 1] contiguous, shared over the batch.
+ *   bias_x : float32 [H, 2 Gx - 1] contiguous.
+ *   Gx     : a power of two in [16, 256];  Gy in [1, 256]  (BINATTN_ERR_SHAPE otherwise).
+ * Everything else as binattn_attend; BINATTN_FLAG_NO_BIAS ignores the tables.
+ */
+int binattn_attend_axial(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
+                         const float *bias_y, const float *bias_x, int Gy, int Gx, float scale, int B,
+                         int H, int N, int d, void *out, const int64_t out_strides[3],
+                         const void *workspace, size_t workspace_bytes, unsigned flags, void *stream);
+
+/*
  * binattn_prepare_kv followed by binattn_attend (all of Alg. 1 after phi);
  * arguments as above.
  */
@@ -134,6 +151,13 @@ int binattn_forward(const uint32_t *q_bits, const uint32_t *k_bits, const float 
                     float scale, int B, int H, int N, int d, void *out,
                     const int64_t out_strides[3], void *workspace, size_t workspace_bytes,
                     unsigned flags, void *stream);
+
+/* binattn_prepare_kv followed by binattn_attend_axial. */
+int binattn_forward_axial(const uint32_t *q_bits, const uint32_t *k_bits, const float *mu_q,
+                          const float *mu_k, const void *v, const int64_t v_strides[3],
+                          const float *bias_y, const float *bias_x, int Gy, int Gx, float scale, int B,
+                          int H, int N, int d, void *out, const int64_t out_strides[3], void *workspace,
+                          size_t workspace_bytes, unsigned flags, void *stream);
 
 /*
  * Integer logits I_ij = s_i . t_j of Sec. 4.1 for query rows

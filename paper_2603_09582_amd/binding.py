@@ -20,8 +20,8 @@ FLAG_NO_MU, FLAG_NO_BIAS = 1, 2
 LOGITS_POPCOUNT, LOGITS_MFMA_I8, LOGITS_MFMA_FP4 = 0, 1, 2
 
 EXPORTS = ["binattn_version", "binattn_strerror", "binattn_pack_qk", "binattn_workspace_bytes",
-           "binattn_prepare_kv", "binattn_attend", "binattn_forward", "binattn_logits_debug",
-           "binattn_quant_v_debug"]
+           "binattn_prepare_kv", "binattn_attend", "binattn_forward", "binattn_attend_axial",
+           "binattn_forward_axial", "binattn_logits_debug", "binattn_quant_v_debug"]
 
 _lib = None
 
@@ -62,6 +62,13 @@ def lib():
     L.binattn_attend.restype = C.c_int
     L.binattn_attend.argtypes = [vp, vp, vp, vp, C.c_int, i64p, C.c_float, C.c_int, C.c_int, C.c_int,
                                  C.c_int, vp, i64p, vp, C.c_size_t, C.c_uint, vp]
+    L.binattn_attend_axial.restype = C.c_int
+    L.binattn_attend_axial.argtypes = [vp, vp, vp, vp, vp, C.c_int, C.c_int, C.c_float, C.c_int, C.c_int,
+                                       C.c_int, C.c_int, vp, i64p, vp, C.c_size_t, C.c_uint, vp]
+    L.binattn_forward_axial.restype = C.c_int
+    L.binattn_forward_axial.argtypes = [vp, vp, vp, vp, vp, i64p, vp, vp, C.c_int, C.c_int, C.c_float,
+                                        C.c_int, C.c_int, C.c_int, C.c_int, vp, i64p, vp, C.c_size_t,
+                                        C.c_uint, vp]
     L.binattn_logits_debug.restype = C.c_int
     L.binattn_logits_debug.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                        vp, C.c_int, vp, C.c_size_t, vp]
@@ -153,6 +160,50 @@ def attend(q_bits: torch.Tensor, mu_q: Optional[torch.Tensor], mu_k: Optional[to
         out.data_ptr(), _strides3(out), workspace.data_ptr(), workspace.numel(), int(flags),
         _stream())
     _check(rc, "binattn_attend")
+    return out
+
+
+def _axial_tables(bias_y: torch.Tensor, bias_x: torch.Tensor, H: int):
+    assert bias_y.dtype == torch.float32 and bias_x.dtype == torch.float32
+    assert bias_y.is_contiguous() and bias_x.is_contiguous() and bias_y.shape[0] == H == bias_x.shape[0]
+    Gy, Gx = (bias_y.shape[1] + 1) // 2, (bias_x.shape[1] + 1) // 2
+    return Gy, Gx
+
+
+def attend_axial(q_bits: torch.Tensor, mu_q: Optional[torch.Tensor], mu_k: Optional[torch.Tensor],
+                 bias_y: torch.Tensor, bias_x: torch.Tensor, scale: float, d: int,
+                 workspace: torch.Tensor, out: Optional[torch.Tensor] = None, flags: int = 0) -> torch.Tensor:
+    """binattn_attend_axial: bias_y fp32 [H, 2Gy-1], bias_x fp32 [H, 2Gx-1]; N = Gy * Gx."""
+    B, H, N, _ = q_bits.shape
+    Gy, Gx = _axial_tables(bias_y, bias_x, H)
+    if out is None:
+        out = torch.empty(B, H, N, d, dtype=torch.bfloat16, device=q_bits.device)
+    rc = lib().binattn_attend_axial(
+        q_bits.data_ptr(), None if mu_q is None else mu_q.data_ptr(),
+        None if mu_k is None else mu_k.data_ptr(), bias_y.data_ptr(), bias_x.data_ptr(), Gy, Gx,
+        float(scale), B, H, N, d, out.data_ptr(), _strides3(out), workspace.data_ptr(),
+        workspace.numel(), int(flags), _stream())
+    _check(rc, "binattn_attend_axial")
+    return out
+
+
+def forward_axial(q_bits: torch.Tensor, k_bits: torch.Tensor, mu_q: Optional[torch.Tensor],
+                  mu_k: Optional[torch.Tensor], v: torch.Tensor, bias_y: torch.Tensor,
+                  bias_x: torch.Tensor, scale: float, out: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None, flags: int = 0) -> torch.Tensor:
+    """binattn_forward_axial = prepare_kv + attend_axial."""
+    B, H, N, d = v.shape
+    Gy, Gx = _axial_tables(bias_y, bias_x, H)
+    if out is None:
+        out = torch.empty(B, H, N, d, dtype=torch.bfloat16, device=v.device)
+    if workspace is None:
+        workspace = alloc_workspace(B, H, N, d, v.device)
+    rc = lib().binattn_forward_axial(
+        q_bits.data_ptr(), k_bits.data_ptr(), None if mu_q is None else mu_q.data_ptr(),
+        None if mu_k is None else mu_k.data_ptr(), v.data_ptr(), _strides3(v), bias_y.data_ptr(),
+        bias_x.data_ptr(), Gy, Gx, float(scale), B, H, N, d, out.data_ptr(), _strides3(out),
+        workspace.data_ptr(), workspace.numel(), int(flags), _stream())
+    _check(rc, "binattn_forward_axial")
     return out
 
 

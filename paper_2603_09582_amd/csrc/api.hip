@@ -93,10 +93,30 @@ int binattn_prepare_kv(const uint32_t *k_bits, const void *v, const int64_t v_st
     return launch_prepare(v, vs, k_bits, s, ws, w, st);
 }
 
-int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k, const void *bias,
-                   int bias_dtype, const int64_t bias_strides[3], float scale, int B, int H, int N,
-                   int d, void *out, const int64_t out_strides[3], const void *workspace,
-                   size_t workspace_bytes, unsigned flags, void *stream) {
+}  // extern "C" (reopened below)
+
+namespace {
+
+struct AxialBias {
+    const float *y, *x;
+    int Gy, Gx;
+};
+
+// BIAS_AXIAL arguments: tables present and aligned, Gx a power of two in [16, 256],
+// Gy in [1, 256], Gy * Gx = N.
+int check_axial(const AxialBias &ax, int N) {
+    if (!ax.y || !ax.x) return BINATTN_ERR_NULL;
+    if (ax.Gy < 1 || ax.Gy > AXIAL_MAX_G || ax.Gx < 16 || ax.Gx > AXIAL_MAX_G ||
+        (ax.Gx & (ax.Gx - 1)) != 0 || (int64_t)ax.Gy * ax.Gx != N)
+        return BINATTN_ERR_SHAPE;
+    if (!aligned(ax.y, 4) || !aligned(ax.x, 4)) return BINATTN_ERR_ALIGN;
+    return BINATTN_OK;
+}
+
+int attend_impl(const uint32_t *q_bits, const float *mu_q, const float *mu_k, const void *bias,
+                int bias_dtype, const int64_t bias_strides[3], const AxialBias *ax, float scale, int B,
+                int H, int N, int d, void *out, const int64_t out_strides[3], const void *workspace,
+                size_t workspace_bytes, unsigned flags, void *stream) {
     if (!q_bits || !out) return BINATTN_ERR_NULL;
     if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
     const Shape s = make_shape(B, H, N, d);
@@ -107,10 +127,16 @@ int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
     if (!aligned(out, 16) || !aligned(q_bits, 4)) return BINATTN_ERR_ALIGN;
     if ((mu_q && !aligned(mu_q, 4)) || (mu_k && !aligned(mu_k, 4))) return BINATTN_ERR_ALIGN;
 
-    const bool use_bias = bias != nullptr && !(flags & BINATTN_FLAG_NO_BIAS);
+    const bool no_bias = (flags & BINATTN_FLAG_NO_BIAS) != 0;
+    const bool use_bias = bias != nullptr && !no_bias;
     int mode = BIAS_NONE;
     Strides3 bs = {0, 0, 0};
-    if (use_bias) {
+    int gx_shift = 0;
+    if (ax != nullptr) {
+        if ((rc = check_axial(*ax, N)) != BINATTN_OK) return rc;
+        while ((1 << gx_shift) < ax->Gx) ++gx_shift;
+        if (!no_bias) mode = BIAS_AXIAL;
+    } else if (use_bias) {
         if (bias_dtype != BINATTN_BIAS_BF16 && bias_dtype != BINATTN_BIAS_F32) return BINATTN_ERR_DTYPE;
         if (!bias_strides) return BINATTN_ERR_NULL;
         for (int i = 0; i < 3; ++i)
@@ -147,6 +173,11 @@ int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
     p.delta = reinterpret_cast<const float *>(ws + w.delta);
     p.B = B; p.H = H; p.N = N; p.d = d;
     p.nblk = s.nblk;
+    p.ax_y = ax ? ax->y : nullptr;
+    p.ax_x = ax ? ax->x : nullptr;
+    p.Gy = ax ? ax->Gy : 0;
+    p.Gx = ax ? ax->Gx : 0;
+    p.gx_shift = gx_shift;
     p.nrb = (N + BR - 1) / BR;
     // Long sequences with a batch-shared, LDS-staged bias: pair batch entries in one
     // workgroup so that the bias stream is fetched once per pair.
@@ -159,6 +190,27 @@ int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
         case 4: return launch_fused_dk<4>(p, mode, st);
         default: return BINATTN_ERR_SHAPE;
     }
+}
+
+}  // namespace
+
+extern "C" {
+
+int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k, const void *bias,
+                   int bias_dtype, const int64_t bias_strides[3], float scale, int B, int H, int N,
+                   int d, void *out, const int64_t out_strides[3], const void *workspace,
+                   size_t workspace_bytes, unsigned flags, void *stream) {
+    return attend_impl(q_bits, mu_q, mu_k, bias, bias_dtype, bias_strides, nullptr, scale, B, H, N, d, out,
+                       out_strides, workspace, workspace_bytes, flags, stream);
+}
+
+int binattn_attend_axial(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
+                         const float *bias_y, const float *bias_x, int Gy, int Gx, float scale, int B,
+                         int H, int N, int d, void *out, const int64_t out_strides[3],
+                         const void *workspace, size_t workspace_bytes, unsigned flags, void *stream) {
+    const AxialBias ax = {bias_y, bias_x, Gy, Gx};
+    return attend_impl(q_bits, mu_q, mu_k, nullptr, 0, nullptr, &ax, scale, B, H, N, d, out, out_strides,
+                       workspace, workspace_bytes, flags, stream);
 }
 
 int binattn_forward(const uint32_t *q_bits, const uint32_t *k_bits, const float *mu_q,
@@ -190,6 +242,31 @@ int binattn_forward(const uint32_t *q_bits, const uint32_t *k_bits, const float 
         return rc;
     return binattn_attend(q_bits, mu_q, mu_k, bias, bias_dtype, bias_strides, scale, B, H, N, d, out,
                           out_strides, workspace, workspace_bytes, flags, stream);
+}
+
+int binattn_forward_axial(const uint32_t *q_bits, const uint32_t *k_bits, const float *mu_q,
+                          const float *mu_k, const void *v, const int64_t v_strides[3],
+                          const float *bias_y, const float *bias_x, int Gy, int Gx, float scale, int B,
+                          int H, int N, int d, void *out, const int64_t out_strides[3], void *workspace,
+                          size_t workspace_bytes, unsigned flags, void *stream) {
+    // Validate the second stage's arguments before the first stage launches anything.
+    if (!q_bits || !k_bits || !v || !out) return BINATTN_ERR_NULL;
+    if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
+    const Shape s = make_shape(B, H, N, d);
+    Strides3 tmp;
+    int rc;
+    if ((rc = check_strides_bhnd(v_strides, s, &tmp)) != BINATTN_OK) return rc;
+    if ((rc = check_strides_bhnd(out_strides, s, &tmp)) != BINATTN_OK) return rc;
+    if (!aligned(v, 16) || !aligned(out, 16) || !aligned(q_bits, 4) || !aligned(k_bits, 4))
+        return BINATTN_ERR_ALIGN;
+    if ((mu_q && !aligned(mu_q, 4)) || (mu_k && !aligned(mu_k, 4))) return BINATTN_ERR_ALIGN;
+    const AxialBias ax = {bias_y, bias_x, Gy, Gx};
+    if ((rc = check_axial(ax, N)) != BINATTN_OK) return rc;
+    if ((rc = binattn_prepare_kv(k_bits, v, v_strides, B, H, N, d, workspace, workspace_bytes,
+                                 stream)) != BINATTN_OK)
+        return rc;
+    return binattn_attend_axial(q_bits, mu_q, mu_k, bias_y, bias_x, Gy, Gx, scale, B, H, N, d, out,
+                                out_strides, workspace, workspace_bytes, flags, stream);
 }
 
 int binattn_logits_debug(const uint32_t *q_bits, const uint32_t *k_bits, int B, int H, int N, int d,

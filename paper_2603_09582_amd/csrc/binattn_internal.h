@@ -130,8 +130,12 @@ enum BiasMode {
     BIAS_NONE = 0,
     BIAS_BF16_VEC = 1,  // any element-aligned rows: 16-byte loads into registers, one block ahead
     BIAS_F32_VEC = 3,   // fp32 bias, 16-byte loads at use
-    BIAS_BF16_LDS = 5   // rows 16-byte aligned, N % 8 == 0: tile staged global -> LDS asynchronously
+    BIAS_BF16_LDS = 5,  // rows 16-byte aligned, N % 8 == 0: tile staged global -> LDS asynchronously
+    BIAS_AXIAL = 7      // b_ij = y[iy - jy] + x[ix - jx] on a Gy x Gx token grid, tables held in LDS
 };
+
+// largest grid side of BIAS_AXIAL (the tables of one head live in LDS)
+constexpr int AXIAL_MAX_G = 256;
 
 struct FusedParams {
     const uint32_t *q_bits;
@@ -145,6 +149,8 @@ struct FusedParams {
     const float *delta;
     int B, H, N, d, nblk, nrb, total_wg;
     int nb;              // batch entries per workgroup (1 or 2)
+    const float *ax_y, *ax_x;  // BIAS_AXIAL: fp32 [H][2 Gy - 1], [H][2 Gx - 1]
+    int Gy, Gx, gx_shift;      // BIAS_AXIAL: token grid, Gx = 1 << gx_shift
 };
 
 // Defined (and explicitly instantiated) in fused_dk<DK>.hip, DK = ceil(d / 32).

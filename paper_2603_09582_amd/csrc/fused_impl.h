@@ -88,6 +88,17 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     // NB = 1: one region per wave, private to it.  NB = 2: two buffers shared by the pair.
     __shared__ __attribute__((aligned(1024))) char biasA[LDS_BIAS ? 4 * 8192 : 1024];
     __shared__ __attribute__((aligned(1024))) char biasB[BIAS_DB ? 4 * 8192 : 1024];
+    // BIAS_AXIAL: the head's two relative-position tables, already divided by alpha.
+    //   axu: four copies of the REVERSED x table, copy j shifted by j entries, so that every
+    //        lane finds its 16-entry window (ascending with the key index) 16-byte aligned.
+    //        Neighbouring queries use copies 3, 2, 1, 0 at one offset, then the next lower
+    //        offset: a copy pitch of 16 entries beyond a multiple of 64 puts the 16-byte reads
+    //        of 16 consecutive lanes on 16 different bank groups.
+    //   axw: the y table (one entry per lane and 16-key tile)
+    constexpr bool AXIAL = MODE == BIAS_AXIAL;
+    constexpr int AXL = 2 * AXIAL_MAX_G + 16;  // pitch of a copy, in entries
+    __shared__ __attribute__((aligned(16))) float axu[AXIAL ? 4 * AXL : 4];
+    __shared__ float axw[AXIAL ? AXL : 4];
     // delta_v of the current item (two copies: consecutive items alternate)
     __shared__ __attribute__((aligned(16))) float sdelta[2][NB][DKP];
 
@@ -154,6 +165,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         bsrc.voff[j] = 0;
         dma_c[j] = (lane & 7) ^ (lane >> 3) ^ ((RGW * bsel + j) & 1);
     }
+    int ax_ub = 0, ax_wb = 0;  // BIAS_AXIAL: this lane's window base in axu (floats), its y-table base
     float m_run, l_run, rho;  // running max (units of T = S / alpha), sum of 255 exp(S - m), rescale sum
     float Of[DK][16];         // output carry, channel 32 cb + 8 (r/4) + 4 g + r % 4
 
@@ -207,6 +219,23 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         if (MODE == BIAS_BF16_VEC || MODE == BIAS_F32_VEC) brow = bias_row_ptr(t);
         if (LDS_BIAS) {
             bsrc = bias_dma_src(t);
+        }
+        if (AXIAL) {
+            // every wave is past the previous item's last block (begin_item follows its closing
+            // barrier), so the tables can be overwritten; a barrier publishes the new ones
+            const int LX = 2 * p.Gx - 1, LY = 2 * p.Gy - 1;
+            const float *ux = p.ax_x + (int64_t)t.h * LX, *wy = p.ax_y + (int64_t)t.h * LY;
+            for (int i = threadIdx.x; i < 4 * AXL; i += FUSED_THREADS * NB) {
+                const int kk = (i % AXL) + (i / AXL);  // index into the reversed table
+                axu[i] = kk < LX ? ux[LX - 1 - kk] * inv_alpha : 0.0f;
+            }
+            for (int i = threadIdx.x; i < AXL; i += FUSED_THREADS * NB) axw[i] = i < LY ? wy[i] * inv_alpha : 0.0f;
+            const int qc = min(q, N - 1);
+            const int ix = qc & (p.Gx - 1), iy = qc >> p.gx_shift;
+            const int s0 = p.Gx - 1 - ix;  // reversed-table index of key column 0
+            ax_ub = (s0 & 3) * AXL + (s0 & ~3);
+            ax_wb = iy + p.Gy - 1;
+            __syncthreads();
         }
         m_run = -INFINITY;
         l_run = 0.0f;
@@ -355,8 +384,29 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         __builtin_amdgcn_sched_barrier(0);  // all of them in flight before the first use
         //    T = I + b / alpha
         v16f T[KT];
+        float wt[KT];  // BIAS_AXIAL: the y term of tile t (constant over its 16 keys), else 0
+        if (AXIAL) {
 #pragma unroll
-        for (int t = 0; t < KT; ++t) T[t] = qk_mfma<DK2>(ka[t], qB, bias_tile(it, t));
+            for (int t = 0; t < KT; ++t) {
+                const int key0 = it * BV + 64 * g + 16 * t;
+                const int jx0 = key0 & (p.Gx - 1), jy = min(key0 >> p.gx_shift, p.Gy - 1);
+                const float *win = axu + ax_ub + jx0;
+                v16f cin;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const f4v x = *reinterpret_cast<const f4v *>(win + 4 * i);
+                    cin[4 * i] = x[0]; cin[4 * i + 1] = x[1]; cin[4 * i + 2] = x[2]; cin[4 * i + 3] = x[3];
+                }
+                wt[t] = axw[ax_wb - jy];
+                T[t] = qk_mfma<DK2>(ka[t], qB, cin);
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < KT; ++t) {
+                wt[t] = 0.0f;
+                T[t] = qk_mfma<DK2>(ka[t], qB, bias_tile(it, t));
+            }
+        }
         __builtin_amdgcn_sched_barrier(0);
         if (MODE == BIAS_BF16_VEC && more)  // braw is free again
             load_bias_vec(sw ? bias_row_ptr(nxt) : brow, nblkidx);
@@ -389,11 +439,23 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         }
 
         // 2. running maximum (Alg. 1: m_ij = max(m_i,j-1, rowmax S_ij))
-        float mx = T[0][0];
+        float mx;
+        if (AXIAL) {  // per-tile maxima, each shifted by the tile's y term
+            mx = -INFINITY;
 #pragma unroll
-        for (int t = 0; t < KT; ++t)
+            for (int t = 0; t < KT; ++t) {
+                float mt = T[t][0];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, T[t][r]);
+                for (int r = 1; r < 16; ++r) mt = fmaxf(mt, T[t][r]);
+                mx = fmaxf(mx, mt + wt[t]);
+            }
+        } else {
+            mx = T[0][0];
+#pragma unroll
+            for (int t = 0; t < KT; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, T[t][r]);
+        }
         const float m_new = fmaxf(m_run, pair_max(mx));
         const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;  // whole row masked so far
         const float resc = __builtin_amdgcn_exp2f((m_run - m_use) * a2);  // e^{m_old - m_new}
@@ -405,12 +467,13 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         v4i pk[KT];
 #pragma unroll
         for (int t = 0; t < KT; ++t) {
+            const float ce = AXIAL ? fmaf(wt[t], a2, cexp) : cexp;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 unsigned w = 0;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const float pe = __builtin_amdgcn_exp2f(fmaf(T[t][4 * i + j], a2, cexp));
+                    const float pe = __builtin_amdgcn_exp2f(fmaf(T[t][4 * i + j], a2, ce));
                     if (j & 1) ls1 += pe; else ls0 += pe;
                     w = __builtin_amdgcn_cvt_pk_u8_f32(pe, j, w);
                 }
@@ -501,7 +564,7 @@ int launch_fused_dk(const FusedParams &p, int mode, hipStream_t stream) {
     }
     switch (mode) {
 #define CASE(M) case M: hipLaunchKernelGGL((fused_kernel<DK, M, 1>), grid, block, 0, stream, p); break;
-        CASE(BIAS_NONE) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC)
+        CASE(BIAS_NONE) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC) CASE(BIAS_AXIAL)
 #undef CASE
         case BIAS_BF16_LDS:
             if constexpr (DK <= 3) {

@@ -88,6 +88,31 @@ def test_forward_rejects_bad_arguments():
     assert fwd(bdt=7, flags=ba.FLAG_NO_BIAS, wsb=100) == -5
 
 
+def fwd_axial(by=FAKE, bx=FAKE, Gy=16, Gx=16, N=256, d=64, qb=FAKE, v=FAKE, out=FAKE, ws=FAKE, wsb=1 << 30,
+              flags=0):
+    B, H = 1, 2
+    s3 = st(H * N * d, N * d, d)
+    return ba.lib().binattn_forward_axial(qb, FAKE, FAKE, FAKE, v, s3, by, bx, Gy, Gx, 0.125, B, H, N, d,
+                                          out, s3, ws, wsb, flags, None)
+
+
+def test_forward_axial_rejects_bad_arguments():
+    assert fwd_axial(by=None) == -1 and fwd_axial(bx=None) == -1 and fwd_axial(qb=None) == -1
+    assert fwd_axial(Gx=24, Gy=16, N=384) == -2      # Gx not a power of two
+    assert fwd_axial(Gx=8, Gy=32) == -2              # Gx below 16
+    assert fwd_axial(Gx=512, Gy=2, N=1024) == -2     # Gx above 256
+    assert fwd_axial(Gx=16, Gy=15) == -2             # Gy * Gx != N
+    assert fwd_axial(Gx=16, Gy=257, N=16 * 257) == -2
+    assert fwd_axial(by=FAKE + 2) == -4 and fwd_axial(bx=FAKE + 1) == -4
+    assert fwd_axial(wsb=100) == -5
+    L = ba.lib()
+    s3 = st(2 * 256 * 64, 256 * 64, 64)
+    assert L.binattn_attend_axial(FAKE, FAKE, FAKE, FAKE, FAKE, 16, 16, 0.125, 1, 2, 256, 64, FAKE, s3, FAKE,
+                                  100, 0, None) == -5
+    assert L.binattn_attend_axial(FAKE, FAKE, FAKE, None, FAKE, 16, 16, 0.125, 1, 2, 256, 64, FAKE, s3, FAKE,
+                                  1 << 30, 0, None) == -1
+
+
 def test_debug_entry_points_reject_bad_arguments():
     L = ba.lib()
     f = lambda **k: L.binattn_logits_debug(

@@ -367,6 +367,55 @@ def test_long_sequence_paired_kernel(kind):
         check_close(got, oracle_forward(x, bias)["O2"], "out vs O2")
 
 
+# ---- decomposed relative-position bias generated in the kernel --------------------------
+def axial_dense(by, bx, Gy, Gx):
+    """The dense [H, N, N] bias the tables stand for: b_ij = by[iy-jy+Gy-1] + bx[ix-jx+Gx-1]."""
+    n = torch.arange(Gy * Gx)
+    iy, ix = n // Gx, n % Gx
+    dy = iy[:, None] - iy[None, :] + Gy - 1
+    dx = ix[:, None] - ix[None, :] + Gx - 1
+    return by[:, dy] + bx[:, dx]
+
+
+@pytest.mark.parametrize("B,H,Gy,Gx,d", [(2, 2, 16, 16, 72), (1, 2, 5, 32, 64), (1, 1, 3, 64, 128),
+                                         (2, 1, 9, 128, 64), (1, 2, 1, 16, 8), (1, 1, 20, 256, 32)])
+def test_axial_bias_matches_dense_oracle(B, H, Gy, Gx, d):
+    N = Gy * Gx
+    say(f"axial bias B={B} H={H} grid {Gy}x{Gx} d={d}")
+    x = small_inputs(B, H, N, d, 500 + Gx)
+    g = torch.Generator().manual_seed(Gy * 1000 + Gx)
+    by = torch.randn(H, 2 * Gy - 1, generator=g) * 0.5
+    bx = torch.randn(H, 2 * Gx - 1, generator=g) * 0.5
+    dense = axial_dense(by, bx, Gy, Gx)                       # fp32 [H, N, N]
+    q, k, v = dev(x.q), dev(x.k), dev(x.v)
+    qb, kb, mq, mk = ba.pack_qk(q, k)
+    out = ba.forward_axial(qb, kb, mq, mk, v, dev(by), dev(bx), x.scale)
+    torch.cuda.synchronize()
+    got = gpu_out_f64(out)
+    if N <= 1024:
+        ref = oracle_algorithm1(x, dense, Bv=128)
+        err = np.abs(got - ref)
+        say(f"    vs Alg.1(Bv=128): max abs err {err.max():.3e}")
+        assert np.all(err <= 2e-3 + 2 ** -7 * np.abs(ref))
+        check_close(got, oracle_forward(x, dense)["O2"], "axial: out vs O2 (dense oracle)")
+    else:
+        rows = np.unique(np.concatenate([np.arange(0, 40), np.arange(N - 40, N),
+                                         np.random.default_rng(3).integers(0, N, 60)]))
+        ref = oracle_forward(x, dense, rows=rows)["O2"]
+        check_close(got[:, :, rows], ref, "axial: sampled rows vs O2 (dense oracle)")
+    # and against the library's own dense path on the same bias
+    out_dense = ba.forward(qb, kb, mq, mk, v, dev(dense), x.scale)
+    torch.cuda.synchronize()
+    diff = np.abs(got - gpu_out_f64(out_dense))
+    say(f"    vs dense fp32 bias path: max abs diff {diff.max():.3e}")
+    assert diff.max() <= 4e-3
+    # the NO_BIAS flag ignores the tables
+    a = ba.forward_axial(qb, kb, mq, mk, v, dev(by), dev(bx), x.scale, flags=ba.FLAG_NO_BIAS)
+    b = ba.forward(qb, kb, mq, mk, v, None, x.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
 # ---- the five workloads ----------------------------------------------------------
 def test_workload_deit_tiny_full():
     w = wl.WORKLOADS["deit_tiny"]
