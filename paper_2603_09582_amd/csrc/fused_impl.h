@@ -320,9 +320,6 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     // One permlane32 swap per dword regroups two such quads so that the lower lane owns 8
     // consecutive channels of quad 2k and the upper lane those of quad 2k + 1: 16-byte stores.
     auto finish_item = [&](const Item &t, const float *dl) {
-        // The epilogue runs once per item; the empty statement below ties its inputs to this
-        // point so that none of its arithmetic is hoisted into the per-block path.
-        asm volatile("" : "+v"(l_run), "+v"(rho), "+v"(dl));
         const float l_tot = pair_sum(l_run);
         const float inv = 1.0f / l_tot;
         const float off = PV_MAGIC_F * rho;
