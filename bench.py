@@ -139,6 +139,17 @@ def run_workload(name, steps, warmup, with_bias=True, axial=False):
         "fused_hbm_bytes": 2 * H * N * N + B * H * N * (W * 4 + 2 * 32 * W + 2 * d),
     }
     res["fused_hbm_gbs"] = res["fused_hbm_bytes"] / (fused_ms * 1e-3) / 1e9
+    if N <= 256 and not axial:  # the single-launch form of the same step (binattn_forward_fused)
+        for _ in range(warmup):
+            ba.forward_fused(x.q, x.k, x.v, x.bias, x.scale, out=out)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            ba.forward_fused(x.q, x.k, x.v, x.bias, x.scale, out=out)
+        torch.cuda.synchronize()
+        one_ms = (time.perf_counter() - t0) * 1e3 / steps
+        res["single_launch_ms_per_step"] = one_ms
+        res["single_launch_tops_equiv"] = w.equiv_ops / (one_ms * 1e-3) / 1e12
     return res, x
 
 

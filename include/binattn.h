@@ -160,6 +160,25 @@ int binattn_forward_axial(const uint32_t *q_bits, const uint32_t *k_bits, const 
                           size_t workspace_bytes, unsigned flags, void *stream);
 
 /*
+ * All of Alg. 1 in ONE launch for short sequences (N <= 256): phi (Eq. 5: sign bits and
+ * abs-means of Q and K), psi (Eq. 7: V codes and delta_v) and the fused loop, one workgroup
+ * per (batch, head) with every intermediate kept on chip.  This is the form for the low
+ * resolutions where Sec. 5.1 finds the separate quantisation passes to cost as much as the
+ * attention itself.  No workspace.
+ *   q, k, v    : bf16 [B, H, N, d] with element strides q_strides / k_strides / v_strides.
+ *   bias, bias_dtype, bias_strides, scale, out, out_strides, flags : as binattn_attend.
+ *   mu_q_out,
+ *   mu_k_out   : optional (may be NULL) float32 [B, H]: the abs-means that were used.
+ * Results equal binattn_pack_qk + binattn_forward up to the summation order of the
+ * abs-means.  N > 256 returns BINATTN_ERR_SHAPE.
+ */
+int binattn_forward_fused(const void *q, const void *k, const void *v, const int64_t q_strides[3],
+                          const int64_t k_strides[3], const int64_t v_strides[3], const void *bias,
+                          int bias_dtype, const int64_t bias_strides[3], float scale, int B, int H, int N,
+                          int d, void *out, const int64_t out_strides[3], float *mu_q_out,
+                          float *mu_k_out, unsigned flags, void *stream);
+
+/*
  * Integer logits I_ij = s_i . t_j of Sec. 4.1 for query rows
  * [row_begin, row_end) of every head: int32 [B, H, row_end - row_begin, N]
  * contiguous.  BINATTN_LOGITS_MFMA_FP4 runs the same tile routine as the fused

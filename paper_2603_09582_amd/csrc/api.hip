@@ -102,6 +102,13 @@ struct AxialBias {
     int Gy, Gx;
 };
 
+// inputs of the single-launch form (binattn_forward_fused)
+struct RawInputs {
+    const void *q, *k, *v;
+    Strides3 qs, ks, vs;
+    float *mu_q_out, *mu_k_out;
+};
+
 // BIAS_AXIAL arguments: tables present and aligned, Gx a power of two in [16, 256],
 // Gy in [1, 256], Gy * Gx = N.
 int check_axial(const AxialBias &ax, int N) {
@@ -113,18 +120,20 @@ int check_axial(const AxialBias &ax, int N) {
     return BINATTN_OK;
 }
 
+// raw == nullptr: the attention stage over a prepared workspace (q_bits, mu_q, mu_k, workspace
+// used).  raw != nullptr: the single-launch form on the bf16 inputs (those four unused).
 int attend_impl(const uint32_t *q_bits, const float *mu_q, const float *mu_k, const void *bias,
-                int bias_dtype, const int64_t bias_strides[3], const AxialBias *ax, float scale, int B,
-                int H, int N, int d, void *out, const int64_t out_strides[3], const void *workspace,
-                size_t workspace_bytes, unsigned flags, void *stream) {
-    if (!q_bits || !out) return BINATTN_ERR_NULL;
+                int bias_dtype, const int64_t bias_strides[3], const AxialBias *ax, const RawInputs *raw,
+                float scale, int B, int H, int N, int d, void *out, const int64_t out_strides[3],
+                const void *workspace, size_t workspace_bytes, unsigned flags, void *stream) {
+    if ((!raw && !q_bits) || !out) return BINATTN_ERR_NULL;
     if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
     const Shape s = make_shape(B, H, N, d);
     const Workspace w = make_workspace(s);
     Strides3 os;
     int rc;
     if ((rc = check_strides_bhnd(out_strides, s, &os)) != BINATTN_OK) return rc;
-    if (!aligned(out, 16) || !aligned(q_bits, 4)) return BINATTN_ERR_ALIGN;
+    if (!aligned(out, 16) || (!raw && !aligned(q_bits, 4))) return BINATTN_ERR_ALIGN;
     if ((mu_q && !aligned(mu_q, 4)) || (mu_k && !aligned(mu_k, 4))) return BINATTN_ERR_ALIGN;
 
     const bool no_bias = (flags & BINATTN_FLAG_NO_BIAS) != 0;
@@ -155,7 +164,7 @@ int attend_impl(const uint32_t *q_bits, const float *mu_q, const float *mu_k, co
             mode = BIAS_F32_VEC;
         }
     }
-    if ((rc = check_workspace(workspace, workspace_bytes, w)) != BINATTN_OK) return rc;
+    if (!raw && (rc = check_workspace(workspace, workspace_bytes, w)) != BINATTN_OK) return rc;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const char *ws = static_cast<const char *>(workspace);
@@ -169,8 +178,8 @@ int attend_impl(const uint32_t *q_bits, const float *mu_q, const float *mu_k, co
     p.scale = scale;
     p.out = static_cast<uint16_t *>(out);
     p.os = os;
-    p.img = ws + w.img;
-    p.delta = reinterpret_cast<const float *>(ws + w.delta);
+    p.img = raw ? nullptr : ws + w.img;
+    p.delta = raw ? nullptr : reinterpret_cast<const float *>(ws + w.delta);
     p.B = B; p.H = H; p.N = N; p.d = d;
     p.nblk = s.nblk;
     p.ax_y = ax ? ax->y : nullptr;
@@ -178,6 +187,27 @@ int attend_impl(const uint32_t *q_bits, const float *mu_q, const float *mu_k, co
     p.Gy = ax ? ax->Gy : 0;
     p.Gx = ax ? ax->Gx : 0;
     p.gx_shift = gx_shift;
+    p.use_mu = use_mu ? 1 : 0;
+    if (raw) {
+        p.xq = static_cast<const uint16_t *>(raw->q);
+        p.xk = static_cast<const uint16_t *>(raw->k);
+        p.xv = static_cast<const uint16_t *>(raw->v);
+        p.xqs = raw->qs; p.xks = raw->ks; p.xvs = raw->vs;
+        p.mu_q_out = raw->mu_q_out; p.mu_k_out = raw->mu_k_out;
+        p.nrb = 1;
+        p.nb = 2;
+        p.total_wg = B * H;
+        switch (s.DK) {
+            case 1: return launch_onehead_dk<1>(p, mode, st);
+            case 2: return launch_onehead_dk<2>(p, mode, st);
+            case 3: return launch_onehead_dk<3>(p, mode, st);
+            case 4: return launch_onehead_dk<4>(p, mode, st);
+            default: return BINATTN_ERR_SHAPE;
+        }
+    }
+    p.xq = p.xk = p.xv = nullptr;
+    p.xqs = p.xks = p.xvs = Strides3{0, 0, 0};
+    p.mu_q_out = p.mu_k_out = nullptr;
     p.nrb = (N + BR - 1) / BR;
     // Long sequences with a batch-shared, LDS-staged bias: pair batch entries in one
     // workgroup so that the bias stream is fetched once per pair.
@@ -200,8 +230,8 @@ int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
                    int bias_dtype, const int64_t bias_strides[3], float scale, int B, int H, int N,
                    int d, void *out, const int64_t out_strides[3], const void *workspace,
                    size_t workspace_bytes, unsigned flags, void *stream) {
-    return attend_impl(q_bits, mu_q, mu_k, bias, bias_dtype, bias_strides, nullptr, scale, B, H, N, d, out,
-                       out_strides, workspace, workspace_bytes, flags, stream);
+    return attend_impl(q_bits, mu_q, mu_k, bias, bias_dtype, bias_strides, nullptr, nullptr, scale, B, H, N, d,
+                       out, out_strides, workspace, workspace_bytes, flags, stream);
 }
 
 int binattn_attend_axial(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
@@ -209,8 +239,8 @@ int binattn_attend_axial(const uint32_t *q_bits, const float *mu_q, const float 
                          int H, int N, int d, void *out, const int64_t out_strides[3],
                          const void *workspace, size_t workspace_bytes, unsigned flags, void *stream) {
     const AxialBias ax = {bias_y, bias_x, Gy, Gx};
-    return attend_impl(q_bits, mu_q, mu_k, nullptr, 0, nullptr, &ax, scale, B, H, N, d, out, out_strides,
-                       workspace, workspace_bytes, flags, stream);
+    return attend_impl(q_bits, mu_q, mu_k, nullptr, 0, nullptr, &ax, nullptr, scale, B, H, N, d, out,
+                       out_strides, workspace, workspace_bytes, flags, stream);
 }
 
 int binattn_forward(const uint32_t *q_bits, const uint32_t *k_bits, const float *mu_q,
@@ -267,6 +297,27 @@ int binattn_forward_axial(const uint32_t *q_bits, const uint32_t *k_bits, const 
         return rc;
     return binattn_attend_axial(q_bits, mu_q, mu_k, bias_y, bias_x, Gy, Gx, scale, B, H, N, d, out,
                                 out_strides, workspace, workspace_bytes, flags, stream);
+}
+
+int binattn_forward_fused(const void *q, const void *k, const void *v, const int64_t q_strides[3],
+                          const int64_t k_strides[3], const int64_t v_strides[3], const void *bias,
+                          int bias_dtype, const int64_t bias_strides[3], float scale, int B, int H, int N,
+                          int d, void *out, const int64_t out_strides[3], float *mu_q_out,
+                          float *mu_k_out, unsigned flags, void *stream) {
+    if (!q || !k || !v || !out) return BINATTN_ERR_NULL;
+    if (!shape_ok(B, H, N, d) || N > 2 * BV) return BINATTN_ERR_SHAPE;
+    const Shape s = make_shape(B, H, N, d);
+    RawInputs raw;
+    int rc;
+    if ((rc = check_strides_bhnd(q_strides, s, &raw.qs)) != BINATTN_OK) return rc;
+    if ((rc = check_strides_bhnd(k_strides, s, &raw.ks)) != BINATTN_OK) return rc;
+    if ((rc = check_strides_bhnd(v_strides, s, &raw.vs)) != BINATTN_OK) return rc;
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16)) return BINATTN_ERR_ALIGN;
+    if ((mu_q_out && !aligned(mu_q_out, 4)) || (mu_k_out && !aligned(mu_k_out, 4))) return BINATTN_ERR_ALIGN;
+    raw.q = q; raw.k = k; raw.v = v;
+    raw.mu_q_out = mu_q_out; raw.mu_k_out = mu_k_out;
+    return attend_impl(nullptr, nullptr, nullptr, bias, bias_dtype, bias_strides, nullptr, &raw, scale, B, H,
+                       N, d, out, out_strides, nullptr, 0, flags, stream);
 }
 
 int binattn_logits_debug(const uint32_t *q_bits, const uint32_t *k_bits, int B, int H, int N, int d,

@@ -149,6 +149,11 @@ struct FusedParams {
     const float *delta;
     int B, H, N, d, nblk, nrb, total_wg;
     int nb;              // batch entries per workgroup (1 or 2)
+    // single-launch short-sequence kernel: the bf16 inputs, whether mu is applied, optional mu exports
+    const uint16_t *xq, *xk, *xv;
+    Strides3 xqs, xks, xvs;
+    int use_mu;
+    float *mu_q_out, *mu_k_out;
     const float *ax_y, *ax_x;  // BIAS_AXIAL: fp32 [H][2 Gy - 1], [H][2 Gx - 1]
     int Gy, Gx, gx_shift;      // BIAS_AXIAL: token grid, Gx = 1 << gx_shift
 };
@@ -156,6 +161,9 @@ struct FusedParams {
 // Defined (and explicitly instantiated) in fused_dk<DK>.hip, DK = ceil(d / 32).
 template <int DK>
 int launch_fused_dk(const FusedParams &p, int mode, hipStream_t stream);
+// The single-launch form for at most two key blocks (nb must be 2, total_wg = B * H).
+template <int DK>
+int launch_onehead_dk(const FusedParams &p, int mode, hipStream_t stream);
 
 inline int check_launch() {
     return hipGetLastError() == hipSuccess ? BINATTN_OK : BINATTN_ERR_LAUNCH;

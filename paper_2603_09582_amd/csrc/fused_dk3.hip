@@ -4,4 +4,5 @@
 
 namespace binattn {
 template int launch_fused_dk<3>(const FusedParams &, int, hipStream_t);
+template int launch_onehead_dk<3>(const FusedParams &, int, hipStream_t);
 }

@@ -32,6 +32,7 @@
 #pragma once
 
 #include "attn_tiles.h"
+#include "quant_v.h"
 
 namespace binattn {
 
@@ -70,23 +71,33 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
 // block (all waves of a workgroup pass it together, right after the barrier, so it is
 // not hidden behind another wave's arithmetic) costs more than it saves: there a
 // workgroup computes one item.
-template <int DK, int MODE, int NB>
+//
+// ONEHEAD (8 waves) is the single-launch form for at most two key blocks: one workgroup
+// owns a whole (batch, head).  It reads the bf16 Q, K, V itself, makes the sign bits, both
+// abs-means, the V codes and both operand images directly in LDS (phi and psi of Alg. 1
+// fused into their consumer), then runs the same block loop on its two 128-row blocks
+// (waves 0-3 / 4-7).  Nothing but the bias and the inputs is read from memory and only the
+// output is written.
+template <int DK, int MODE, int NB, bool ONEHEAD = false>
 __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const FusedParams p) {
     using L = Image<DK>;
+    static_assert(!ONEHEAD || NB == 2, "the single-launch form uses 8 waves");
+    constexpr bool PAIR = NB == 2 && !ONEHEAD;  // two batch entries sharing bias tiles
+    constexpr int NIMG = PAIR ? 2 : 1;          // operand images per buffer
     constexpr bool PERSIST = NB == 1;
     constexpr int DKP = 32 * DK;
     constexpr int DK2 = L::DK2;
     constexpr bool LDS_BIAS = MODE == BIAS_BF16_LDS;
-    constexpr bool BIAS_DB = LDS_BIAS && NB == 2;  // bias tiles double-buffered and shared
+    constexpr bool BIAS_DB = LDS_BIAS && PAIR;  // bias tiles double-buffered and shared
     // V operand rows of this many channel blocks are fetched from LDS before the
     // exponential phase (the rest just before their MFMAs): hides the LDS latency
     // where the register budget allows it.
     constexpr int PRE = DK <= 2 ? DK : 1;
-    __shared__ __attribute__((aligned(1024))) char bufA[NB * L::BYTES];
-    __shared__ __attribute__((aligned(1024))) char bufB[NB * L::BYTES];
+    __shared__ __attribute__((aligned(1024))) char bufA[NIMG * L::BYTES];
+    __shared__ __attribute__((aligned(1024))) char bufB[NIMG * L::BYTES];
     // BIAS_BF16_LDS: staging of the 32 x 128 bias tiles, 8 KiB per 32-row group.
     // NB = 1: one region per wave, private to it.  NB = 2: two buffers shared by the pair.
-    __shared__ __attribute__((aligned(1024))) char biasA[LDS_BIAS ? 4 * 8192 : 1024];
+    __shared__ __attribute__((aligned(1024))) char biasA[LDS_BIAS ? (ONEHEAD ? 8 : 4) * 8192 : 1024];
     __shared__ __attribute__((aligned(1024))) char biasB[BIAS_DB ? 4 * 8192 : 1024];
     // BIAS_AXIAL: the head's two relative-position tables, already divided by alpha.
     //   axu: four copies of the REVERSED x table, copy j shifted by j entries, so that every
@@ -100,14 +111,16 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     __shared__ __attribute__((aligned(16))) float axu[AXIAL ? 4 * AXL : 4];
     __shared__ float axw[AXIAL ? AXL : 4];
     // delta_v of the current item (two copies: consecutive items alternate)
-    __shared__ __attribute__((aligned(16))) float sdelta[2][NB][DKP];
+    __shared__ __attribute__((aligned(16))) float sdelta[2][NIMG][DKP];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) & 3);  // 32-row group
-    const int bsel = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);        // batch entry in the workgroup
+    const int bsel = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);        // half of the workgroup
+    const int isel = PAIR ? bsel : 0;                // which resident image / delta copy
+    const int wreg = ONEHEAD ? 4 * bsel + wave : wave;  // this wave's private bias region
     const int m = lane & 31, g = lane >> 5;
     const int N = p.N, d = p.d, W = (d + 31) / 32;
-    const int nbp = p.B / NB;
+    const int nbp = p.B / NIMG;
     const int per_xcd = (p.total_wg + 7) >> 3;
     const int vmax = 8 * per_xcd;
     const int bsb = (MODE == BIAS_F32_VEC) ? 4 : 2;  // bytes per bias element
@@ -125,9 +138,9 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         const int u = (v & 7) * per_xcd + (v >> 3);
         t.valid = v < vmax && u < p.total_wg;
         const int uu = t.valid ? u : 0;
-        t.b = (uu % nbp) * NB + bsel;
-        t.rb = (uu / nbp) % p.nrb;
-        t.h = uu / (nbp * p.nrb);
+        t.b = ONEHEAD ? uu / p.H : (uu % nbp) * NIMG + isel;
+        t.rb = ONEHEAD ? bsel : (uu / nbp) % p.nrb;
+        t.h = ONEHEAD ? uu % p.H : uu / (nbp * p.nrb);
         t.bh = t.b * p.H + t.h;
         return t;
     };
@@ -150,7 +163,8 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     // 16 different 16-byte bank groups of the 256-byte LDS row.
     // A wave copies RGW of the four 8-row groups of its 32-row tile: all four when the
     // tile is its own (NB = 1), two when the tile is shared with the other batch entry.
-    constexpr int RGW = 4 / NB;
+    constexpr int RGW = PAIR ? 2 : 4;
+    const int rg0 = PAIR ? RGW * bsel : 0;  // first row group of the tile this wave copies
     // The copy address is a wave-uniform base (first row of the group, scalar registers,
     // advanced by scalar arithmetic) plus a 32-bit lane offset that is fixed for an item.
     struct BiasSrc {
@@ -163,7 +177,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     for (int j = 0; j < RGW; ++j) {
         bsrc.base[j] = nullptr;
         bsrc.voff[j] = 0;
-        dma_c[j] = (lane & 7) ^ (lane >> 3) ^ ((RGW * bsel + j) & 1);
+        dma_c[j] = (lane & 7) ^ (lane >> 3) ^ ((rg0 + j) & 1);
     }
     int ax_ub = 0, ax_wb = 0;  // BIAS_AXIAL: this lane's window base in axu (floats), its y-table base
     float m_run, l_run, rho;  // running max (units of T = S / alpha), sum of 255 exp(S - m), rescale sum
@@ -190,7 +204,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         BiasSrc o;
 #pragma unroll
         for (int j = 0; j < RGW; ++j) {
-            const int rg = RGW * bsel + j;
+            const int rg = rg0 + j;
             const int r = (lane >> 3) ^ (rg & 1);
             const int row0 = min(t.rb * BR + wave * ROWS_PER_WAVE + 8 * rg, N - 1);  // uniform
             const int row = min(row0 + r, N - 1);
@@ -255,7 +269,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
                 const int key0 = blk * BV + 64 * gh + 8 * dma_c[j];
                 if (key0 + 8 <= N)
                     dma16(src.base[j] + (blk * BV + 64 * gh) * 2, src.voff[j],
-                          region + ((RGW * bsel + j) * 2 + gh) * 1024);
+                          region + ((rg0 + j) * 2 + gh) * 1024);
             }
     };
     u4v braw[8];  // the 64 bf16 bias values of this lane for the current block
@@ -363,10 +377,10 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         const char *nimg = sw ? image_ptr(nxt) : imgs + (int64_t)(it + 1) * L::BYTES;
         const int nblkidx = sw ? 0 : it + 1;
         const BiasSrc nsrc = (LDS_BIAS && sw) ? bias_dma_src(nxt) : bsrc;
-        if (more) dma_image<DK>(nimg, inxt + bsel * L::BYTES, wave, lane);
+        if (!ONEHEAD && more) dma_image<DK>(nimg, inxt + isel * L::BYTES, wave, lane);
         if (BIAS_DB && more) dma_bias(nsrc, nblkidx, bnxt);
-        if (it == 0 && wave == 0 && lane < DKP / 4)  // delta_v of this item, for its epilogue
-            dma16(p.delta + (int64_t)cur.bh * DKP, 16 * lane, lds_offset(&sdelta[parity][bsel][0]));
+        if (!ONEHEAD && it == 0 && wave == 0 && lane < DKP / 4)  // delta_v of this item, for its epilogue
+            dma16(p.delta + (int64_t)cur.bh * DKP, 16 * lane, lds_offset(&sdelta[parity][isel][0]));
         if (sw && nxt.valid) fetch_item_regs(nxt);
 
         // 1. all LDS reads of the logit phase go out together: bias tile, key rows
@@ -515,7 +529,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
             ++it;
             return true;
         }
-        finish_item(cur, &sdelta[parity][bsel][0]);
+        finish_item(cur, &sdelta[parity][isel][0]);
         if (!PERSIST || !nxt.valid) return false;
         cur = nxt;
         v += gridDim.x;
@@ -527,16 +541,154 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     };
 
     // ---- prologue: first block of the first item --------------------------------
-    const char *bA = biasA + wave * 8192, *bB = BIAS_DB ? biasB + wave * 8192 : bA;
-    dma_image<DK>(image_ptr(cur), lds_offset(bufA) + bsel * L::BYTES, wave, lane);
-    fetch_item_regs(cur);
+    const char *bA = biasA + wreg * 8192, *bB = BIAS_DB ? biasB + wave * 8192 : bA;
+    if constexpr (ONEHEAD) {
+        // phi and psi of Alg. 1 for this head, straight into the two LDS images.
+        constexpr int NT = FUSED_THREADS * NB;
+        __shared__ int sabs[DKP];            // per-channel absmax of V (bit patterns)
+        __shared__ float srcp[DKP], sthr[DKP];
+        __shared__ float ssum[2][NT / 64];   // |q| and |k| partial sums per wave
+        const int C16 = d / 8, nblk = p.nblk;
+        auto imgp = [&](int blk) -> char * { return blk ? bufB : bufA; };
+        const uint16_t *qb_ = p.xq + (int64_t)cur.b * p.xqs.b + (int64_t)cur.h * p.xqs.h;
+        const uint16_t *kb_ = p.xk + (int64_t)cur.b * p.xks.b + (int64_t)cur.h * p.xks.h;
+        const uint16_t *vb_ = p.xv + (int64_t)cur.b * p.xvs.b + (int64_t)cur.h * p.xvs.h;
+
+        // V rows into registers: a thread owns quads of consecutive tokens of one 8-channel
+        // chunk; consecutive lanes take consecutive chunks (whole-row loads)
+        const int RT = NT / C16;              // thread groups = token quads per pass (>= 32)
+        const int vc = threadIdx.x % C16, vr = threadIdx.x / C16;
+        const bool von = vr < RT;
+        u4 vw[2][4];
+#pragma unroll
+        for (int kq = 0; kq < 2; ++kq)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int row = 4 * (vr + kq * RT) + t;
+                vw[kq][t] = u4{0u, 0u, 0u, 0u};
+                if (von && row < N && vr + kq * RT < 2 * BV / 4)
+                    vw[kq][t] = *reinterpret_cast<const u4 *>(vb_ + (int64_t)row * p.xvs.n + 8 * vc);
+            }
+        // this lane's query row: the sign words its B operand needs (channels 64 s + 32 g + ..)
+        const int qrow = cur.rb * BR + wave * ROWS_PER_WAVE + m;
+        float qsum = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 2 * DK2; ++w) pend_q[w] = 0u;
+#pragma unroll
+        for (int sI = 0; sI < DK2; ++sI) {
+            unsigned word = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int c0 = 32 * (2 * sI + g) + 8 * j;
+                if (qrow < N && c0 < d) {
+                    const u4 x = *reinterpret_cast<const u4 *>(qb_ + (int64_t)qrow * p.xqs.n + c0);
+                    word |= sign_bits8_abs(x, qsum) << (8 * j);
+                }
+            }
+            if (g) pend_q[2 * sI + 1] = word; else pend_q[2 * sI] = word;
+        }
+        // clear both images, the absmax cells
+        for (int i = threadIdx.x; i < L::BYTES / 4; i += NT) {
+            reinterpret_cast<unsigned *>(bufA)[i] = 0u;
+            reinterpret_cast<unsigned *>(bufB)[i] = 0u;
+        }
+        if (threadIdx.x < DKP) sabs[threadIdx.x] = 0;
+        __syncthreads();
+        // keys: sign bits -> FP4 codes of +-1 at the row position the QK tile reads
+        float ksum = 0.0f;
+        for (int i = threadIdx.x; i < nblk * BV * C16; i += NT) {
+            const int c8 = i % C16, pos = (i / C16) % BV, blk = i / (C16 * BV);
+            const int key = blk * BV + key_of_position(pos);
+            if (key < N) {
+                const u4 x = *reinterpret_cast<const u4 *>(kb_ + (int64_t)key * p.xks.n + 8 * c8);
+                const unsigned bits = sign_bits8_abs(x, ksum);
+                *reinterpret_cast<unsigned *>(imgp(blk) + L::K_OFF + pos * L::KP +
+                                              16 * k_chunk(pos, c8 >> 2, L::KP) + 4 * (c8 & 3)) =
+                    fp4_pm1_from_bits8(bits);
+            }
+        }
+        // V: absmax per channel through LDS integer maxima
+        if (von) {
+            unsigned mb[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int kq = 0; kq < 2; ++kq)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) absmax_acc(mb, vw[kq][t]);
+            float mf[8];
+            absmax_floats(mb, mf);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (mf[i] > 0.0f) atomicMax(&sabs[8 * vc + i], __float_as_int(mf[i]));
+        }
+        // abs-means: wave sums, then the eight partials
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            qsum += __shfl_down(qsum, off, 64);
+            ksum += __shfl_down(ksum, off, 64);
+        }
+        if (lane == 0) {
+            ssum[0][threadIdx.x >> 6] = qsum;
+            ssum[1][threadIdx.x >> 6] = ksum;
+        }
+        __syncthreads();
+        if (threadIdx.x < 8 * C16) {
+            float dl;
+            quant_consts(__int_as_float(sabs[threadIdx.x]), &dl, &srcp[threadIdx.x], &sthr[threadIdx.x]);
+            sdelta[0][0][threadIdx.x] = dl;
+        }
+        float tq = 0.0f, tk = 0.0f;
+#pragma unroll
+        for (int i = 0; i < NT / 64; ++i) {
+            tq += ssum[0][i];
+            tk += ssum[1][i];
+        }
+        const float inv_cnt = 1.0f / ((float)N * (float)d);
+        pend_muq = p.use_mu ? tq * inv_cnt : 1.0f;
+        pend_muk = p.use_mu ? tk * inv_cnt : 1.0f;
+        if (threadIdx.x == 0) {
+            if (p.mu_q_out) p.mu_q_out[cur.bh] = tq * inv_cnt;
+            if (p.mu_k_out) p.mu_k_out[cur.bh] = tk * inv_cnt;
+        }
+        __syncthreads();
+        // V codes, channel-major, into the images
+        if (von) {
+#pragma unroll
+            for (int kq = 0; kq < 2; ++kq) {
+                const int quad = vr + kq * RT;
+                if (4 * quad < N && quad < 2 * BV / 4) {
+                    unsigned packed[8];
+                    quant_quad(vw[kq], &sdelta[0][0][0], srcp, sthr, vc, packed);
+                    char *dstv = imgp(quad / (BV / 4)) + L::V_OFF + 4 * (quad % (BV / 4));
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        *reinterpret_cast<unsigned *>(dstv + (8 * vc + i) * L::VP) = packed[i];
+                }
+            }
+        }
+        __syncthreads();
+        // accumulator seeds: 128 * column sums + the float-bit offset
+        if (threadIdx.x < nblk * DKP) {
+            const int blk = threadIdx.x / DKP, ch = threadIdx.x % DKP;
+            int sum = 0;
+#pragma unroll
+            for (int j = 0; j < BV / 16; ++j) {
+                const u4 x = *reinterpret_cast<const u4 *>(imgp(blk) + L::V_OFF + ch * L::VP + 16 * j);
+#pragma unroll
+                for (int n = 0; n < 4; ++n) sum = __builtin_amdgcn_sdot4((int)x[n], 0x01010101, sum, false);
+            }
+            reinterpret_cast<int *>(imgp(blk) + L::CS_OFF)[ch] = PV_MAGIC_BITS + 128 * sum;
+        }
+    } else {
+        dma_image<DK>(image_ptr(cur), lds_offset(bufA) + isel * L::BYTES, wave, lane);
+        fetch_item_regs(cur);
+    }
     begin_item(cur);
     if (MODE == BIAS_BF16_VEC) load_bias_vec(brow, 0);
     if (LDS_BIAS) dma_bias(bsrc, 0, lds_offset(bA));
     wait_vmem();
     __syncthreads();
 
-    const char *imgA = bufA + bsel * L::BYTES, *imgB = bufB + bsel * L::BYTES;
+    const char *imgA = bufA + isel * L::BYTES, *imgB = bufB + isel * L::BYTES;
     for (;;) {
         if (!step(imgA, lds_offset(bufB), bA, lds_offset(bB))) break;
         if (!step(imgB, lds_offset(bufA), bB, lds_offset(bA))) break;
@@ -566,6 +718,25 @@ int launch_fused_dk(const FusedParams &p, int mode, hipStream_t stream) {
         case BIAS_BF16_LDS:
             if constexpr (DK <= 3) {
                 hipLaunchKernelGGL((fused_kernel<DK, BIAS_BF16_LDS, 1>), grid, block, 0, stream, p);
+                break;
+            }
+            return BINATTN_ERR_SHAPE;
+        default: return BINATTN_ERR_DTYPE;
+    }
+    return check_launch();
+}
+
+template <int DK>
+int launch_onehead_dk(const FusedParams &p, int mode, hipStream_t stream) {
+    const int needed = ((p.total_wg + 7) / 8) * 8;
+    const dim3 grid((unsigned)needed), block(FUSED_THREADS * 2);
+    switch (mode) {
+#define CASE(M) case M: hipLaunchKernelGGL((fused_kernel<DK, M, 2, true>), grid, block, 0, stream, p); break;
+        CASE(BIAS_NONE) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC) CASE(BIAS_AXIAL)
+#undef CASE
+        case BIAS_BF16_LDS:
+            if constexpr (DK <= 3) {
+                hipLaunchKernelGGL((fused_kernel<DK, BIAS_BF16_LDS, 2, true>), grid, block, 0, stream, p);
                 break;
             }
             return BINATTN_ERR_SHAPE;

@@ -7,12 +7,11 @@
 //     codes stored channel-major, and the accumulator seed of the P.V
 //     contraction (128 * column sums per key block, see fused_impl.h)
 // All are HBM-bound streaming kernels.
-#include "binattn_internal.h"
+#include "quant_v.h"
 
 namespace binattn {
 
 constexpr int PREP_THREADS = 256;
-typedef unsigned u4 __attribute__((ext_vector_type(4)));
 
 // 8 sign bits -> 8 FP4 (e2m1) nibbles: +1.0 (0x2) where set, -1.0 (0xA) where clear.
 __device__ __forceinline__ unsigned fp4_pm1_bits8(unsigned b) {
@@ -20,18 +19,6 @@ __device__ __forceinline__ unsigned fp4_pm1_bits8(unsigned b) {
     x = (x | (x << 6)) & 0x03030303u;
     x = (x | (x << 3)) & 0x11111111u;
     return 0xAAAAAAAAu - (x << 3);
-}
-
-// Row position inside a key block <-> key offset.  The fused kernel's lane
-// (g = lane / 32) holds, for MFMA tile t and accumulator register r, the key
-// j0 + 64 g + 16 t + r; the MFMA puts accumulator register r of lane group g
-// at tile row m = 8 (r / 4) + 4 g + (r % 4).  Rows are stored at position
-// 32 t + m so that the A operand reads consecutive LDS rows.
-__device__ __forceinline__ int key_of_position(int pos) {
-    const int t = pos >> 5, m = pos & 31;
-    const int g = (m >> 2) & 1;
-    const int r = ((m >> 3) << 2) | (m & 3);
-    return 64 * g + 16 * t + r;
 }
 
 // Key block `blk` of one head: sign words -> FP4 rows of the block image.
@@ -60,29 +47,6 @@ __global__ __launch_bounds__(PREP_THREADS) void expand_k_kernel(const uint32_t *
     const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
     expand_k_block(k_bits + (int64_t)bh * N * W, N, d, W, blk, KP,
                    img + ((int64_t)bh * nblk + blk) * img_bytes);
-}
-
-__device__ __forceinline__ void unpack8(u4 w, float f[8]) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        f[2 * i] = __uint_as_float(w[i] << 16);
-        f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-    }
-}
-
-// Running absmax of 8 bf16 values per lane on their bit patterns: with the sign bit
-// cleared, bf16 magnitudes order like 16-bit unsigned integers (two values per instruction).
-typedef unsigned short us2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ void absmax_acc(unsigned m[4], u4 w) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const us2 a = __builtin_bit_cast(us2, m[i]);
-        const us2 b = __builtin_bit_cast(us2, w[i] & 0x7FFF7FFFu);
-        m[i] = __builtin_bit_cast(unsigned, __builtin_elementwise_max(a, b));
-    }
-}
-__device__ __forceinline__ void absmax_floats(const unsigned m[4], float f[8]) {
-    unpack8(u4{m[0], m[1], m[2], m[3]}, f);
 }
 
 // absmax over token rows [n0, n1) of one head, all threads of the workgroup:
@@ -118,55 +82,6 @@ __device__ __forceinline__ float absmax_rows(const uint16_t *__restrict__ vb, in
     if (threadIdx.x < D)
         for (int r = 0; r < RT; ++r) a = fmaxf(a, smax[r * D + threadIdx.x]);
     return a;
-}
-
-// Eq. 7 scale: absmax / 127 (IEEE fp32 division); 1 for an all-zero channel.
-__device__ __forceinline__ float delta_of_absmax(float a) {
-    return (a == 0.0f) ? 1.0f : __fdiv_rn(a, 127.0f);
-}
-
-// Eq. 7: code = round-to-nearest-even(v / delta), clamped to [-127, 127], where the
-// quotient is the IEEE fp32 one.  t = v * (1 / delta) is within 2.3e-5 of that quotient
-// (|v / delta| <= 127), so its rounding is already decided unless t sits that close to a
-// half-integer; only then is the exact division needed.  Clamping t first is equivalent
-// (the bounds are integers).  Rounding is the fp32 addition of 1.5 * 2^23, whose result
-// carries the two's complement code in its low byte.  thr = 0.4999 normally; a channel whose
-// 1 / delta is not finite passes thr < 0 and rcp = 0, which sends every element to the division.
-constexpr float QMAGIC = 12582912.0f;  // 1.5 * 2^23
-__device__ __forceinline__ unsigned quant_bits(float v, float delta, float rcp_delta, float thr) {
-    const float t = __builtin_amdgcn_fmed3f(v * rcp_delta, -127.0f, 127.0f);
-    float s = t + QMAGIC;
-    const float q = s - QMAGIC;
-    if (fabsf(t - q) > thr) {
-        const float e = fminf(fmaxf(rintf(__fdiv_rn(v, delta)), -127.0f), 127.0f);
-        s = e + QMAGIC;
-    }
-    return __float_as_uint(s);
-}
-// codes of 4 tokens x 8 channels (w[k]: token k), one dword per channel, token k in byte k
-__device__ __forceinline__ void quant_quad(const u4 w[4], const float *sdelta, const float *srcp,
-                                           const float *sthr, int c, unsigned packed[8]) {
-    float f[4][8];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) unpack8(w[k], f[k]);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const float dl = sdelta[8 * c + i], rc = srcp[8 * c + i], th = sthr[8 * c + i];
-        unsigned b[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) b[k] = quant_bits(f[k][i], dl, rc, th);
-        const unsigned lo = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
-        const unsigned hi = __builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u);
-        packed[i] = lo | (hi << 16);
-    }
-}
-// per-channel constants of the quantiser from the channel's absmax
-__device__ __forceinline__ void quant_consts(float a, float *dl, float *rc, float *th) {
-    *dl = delta_of_absmax(a);
-    const float r = __fdiv_rn(1.0f, *dl);
-    const bool ok = r < 3.0e38f;
-    *rc = ok ? r : 0.0f;
-    *th = ok ? 0.4999f : -1.0f;
 }
 
 // Key block `blk` of one head: codes (channel-major) and the accumulator seeds

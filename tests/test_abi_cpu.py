@@ -113,6 +113,22 @@ def test_forward_axial_rejects_bad_arguments():
                                   1 << 30, 0, None) == -1
 
 
+def fused(q=FAKE, k=FAKE, v=FAKE, out=FAKE, N=200, d=64, bias=FAKE, bdt=1, bs=None, qs=None, mq=FAKE, flags=0):
+    B, H = 2, 2
+    s3 = st(H * N * d, N * d, d)
+    return ba.lib().binattn_forward_fused(q, k, v, qs or s3, s3, s3, bias, bdt, bs or st(0, N * N, N), 0.125, B, H,
+                                          N, d, out, s3, mq, None, flags, None)
+
+
+def test_forward_fused_rejects_bad_arguments():
+    assert fused(q=None) == -1 and fused(k=None) == -1 and fused(v=None) == -1 and fused(out=None) == -1
+    assert fused(N=257) == -2 and fused(N=0) == -2 and fused(d=20) == -2
+    assert fused(qs=st(2048, 1024, 60)) == -3
+    assert fused(q=FAKE + 8) == -4 and fused(mq=FAKE + 2) == -4 and fused(out=FAKE + 2) == -4
+    assert fused(bdt=9) == -6
+    assert fused(bs=st(0, 100, 8)) == -3
+
+
 def test_debug_entry_points_reject_bad_arguments():
     L = ba.lib()
     f = lambda **k: L.binattn_logits_debug(

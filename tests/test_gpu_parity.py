@@ -463,6 +463,81 @@ def test_hip_graph_replay_matches_eager():
     check_close(gpu_out_f64(out)[:, :, ::37], ref, "graph test, last inputs vs O2")
 
 
+# ---- the single-launch form for short sequences -------------------------------------------
+FUSED_SHAPES = [(1, 2, 1, 64), (1, 2, 2, 8), (2, 1, 63, 64), (1, 2, 64, 72), (1, 1, 65, 128), (1, 3, 129, 64),
+                (2, 2, 197, 64), (1, 2, 255, 72), (3, 2, 256, 72), (1, 1, 256, 128), (1, 2, 136, 96),
+                (2, 1, 200, 16), (1, 1, 130, 104)]
+
+
+@pytest.mark.parametrize("B,H,N,d", FUSED_SHAPES)
+def test_forward_fused_matches_oracle(B, H, N, d):
+    say(f"single-launch forward B={B} H={H} N={N} d={d}")
+    x = small_inputs(B, H, N, d, 40 + N)
+    mq = torch.zeros(B, H, dtype=torch.float32, device="cuda")
+    mk = torch.zeros_like(mq)
+    out = ba.forward_fused(dev(x.q), dev(x.k), dev(x.v), dev(x.bias), x.scale, mu_q=mq, mu_k=mk)
+    torch.cuda.synchronize()
+    got = gpu_out_f64(out)
+    for b in range(B):
+        for h in range(H):
+            assert float(mq[b, h]) == pytest.approx(orc.abs_mean(np_bits(x.q[b, h])), rel=2e-6)
+            assert float(mk[b, h]) == pytest.approx(orc.abs_mean(np_bits(x.k[b, h])), rel=2e-6)
+    check_close(got, oracle_forward(x, x.bias)["O2"], "out vs O2")
+    alg = oracle_algorithm1(x, x.bias, Bv=128)
+    err = np.abs(got - alg)
+    say(f"    vs Alg.1(Bv=128): max abs err {err.max():.3e}")
+    assert np.all(err <= 2e-3 + 2 ** -7 * np.abs(alg))
+    # and against the three-call path of the library
+    three = run_forward(x, x.bias)
+    assert np.abs(got - three).max() <= 2e-3
+
+
+@pytest.mark.parametrize("kind", ["none", "f32", "bf16_per_batch", "bf16_padded_rows", "no_mu", "flag_no_bias",
+                                  "strided"])
+def test_forward_fused_bias_modes_and_flags(kind):
+    B, H, N, d = 2, 2, 200, 64
+    say(f"single-launch forward mode {kind}")
+    x = small_inputs(B, H, N, d, 77)
+    g = torch.Generator().manual_seed(5)
+    bias, flags, use_mu, obias = dev(x.bias), 0, True, x.bias
+    q, k, v = dev(x.q), dev(x.k), dev(x.v)
+    if kind == "none":
+        bias = obias = None
+    elif kind == "f32":
+        obias = torch.randn(H, N, N, generator=g) * 0.3
+        bias = dev(obias)
+    elif kind == "bf16_per_batch":
+        obias = (torch.randn(B, H, N, N, generator=g) * 0.3).to(torch.bfloat16)
+        bias = dev(obias)
+    elif kind == "bf16_padded_rows":
+        store = torch.zeros(H, N, 208, dtype=torch.bfloat16, device="cuda")
+        store[:, :, :N] = dev(x.bias)
+        bias = store[:, :, :N]
+    elif kind == "no_mu":
+        flags, use_mu = ba.FLAG_NO_MU, False
+    elif kind == "flag_no_bias":
+        flags, obias = ba.FLAG_NO_BIAS, None
+    elif kind == "strided":                      # [B, N, H, d] storage seen as [B, H, N, d]
+        q, k, v = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (q, k, v))
+    out = ba.forward_fused(q, k, v, bias, x.scale, flags=flags)
+    torch.cuda.synchronize()
+    check_close(gpu_out_f64(out), oracle_forward(x, obias, use_mu=use_mu)["O2"], f"{kind}: out vs O2")
+
+
+def test_forward_fused_workload_dit_xl2_256_sampled_heads():
+    w = wl.WORKLOADS["dit_xl2_256"]
+    say("single-launch forward on dit_xl2_256")
+    x = wl.make_inputs(w, device="cuda")
+    out = ba.forward_fused(x.q, x.k, x.v, x.bias, x.scale)
+    torch.cuda.synchronize()
+    for (b, h) in [(0, 0), (31, 15), (13, 7)]:
+        q, k, v = (np_bits(t[b, h].cpu()) for t in (x.q, x.k, x.v))
+        vq, delta = orc.quant_v(v)
+        o = orc.attention_rows(q, k, v, np_bits(x.bias[h].cpu()), x.scale, orc.abs_mean(q), orc.abs_mean(k),
+                               vq, delta, want=("O2",))
+        check_close(gpu_out_f64(out[b, h]), o["O2"], f"dit_xl2_256 head {(b, h)} vs O2")
+
+
 # ---- the five workloads ----------------------------------------------------------
 def test_workload_deit_tiny_full():
     w = wl.WORKLOADS["deit_tiny"]
