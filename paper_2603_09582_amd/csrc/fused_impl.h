@@ -587,6 +587,24 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
             }
             if (g) pend_q[2 * sI + 1] = word; else pend_q[2 * sI] = word;
         }
+        // this thread's key chunks (8 channels of one key each), loaded before the first barrier
+        constexpr int KPT = (2 * BV * 4 * DK + NT - 1) / NT;  // chunks per thread, at most
+        u4 kx[KPT];
+#pragma unroll
+        for (int kk = 0; kk < KPT; ++kk) {
+            const int i = threadIdx.x + kk * NT;
+            const int c8 = i % C16, pos = (i / C16) % BV, blk = i / (C16 * BV);
+            const int key = blk * BV + key_of_position(pos);
+            kx[kk] = u4{0u, 0u, 0u, 0u};
+            if (blk < nblk && key < N)
+                kx[kk] = *reinterpret_cast<const u4 *>(kb_ + (int64_t)key * p.xks.n + 8 * c8);
+        }
+        // the first bias tile / bias registers do not depend on anything computed here
+        if (LDS_BIAS) {
+            bsrc = bias_dma_src(cur);
+            dma_bias(bsrc, 0, lds_offset(bA));
+        }
+        if (MODE == BIAS_BF16_VEC) load_bias_vec(bias_row_ptr(cur), 0);
         // clear both images, the absmax cells
         for (int i = threadIdx.x; i < L::BYTES / 4; i += NT) {
             reinterpret_cast<unsigned *>(bufA)[i] = 0u;
@@ -596,17 +614,21 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         __syncthreads();
         // keys: sign bits -> FP4 codes of +-1 at the row position the QK tile reads
         float ksum = 0.0f;
-        for (int i = threadIdx.x; i < nblk * BV * C16; i += NT) {
+#pragma unroll
+        for (int kk = 0; kk < KPT; ++kk) {
+            const int i = threadIdx.x + kk * NT;
             const int c8 = i % C16, pos = (i / C16) % BV, blk = i / (C16 * BV);
             const int key = blk * BV + key_of_position(pos);
-            if (key < N) {
-                const u4 x = *reinterpret_cast<const u4 *>(kb_ + (int64_t)key * p.xks.n + 8 * c8);
-                const unsigned bits = sign_bits8_abs(x, ksum);
+            if (blk < nblk && key < N) {
+                const unsigned bits = sign_bits8_abs(kx[kk], ksum);
                 *reinterpret_cast<unsigned *>(imgp(blk) + L::K_OFF + pos * L::KP +
                                               16 * k_chunk(pos, c8 >> 2, L::KP) + 4 * (c8 & 3)) =
                     fp4_pm1_from_bits8(bits);
             }
         }
+        // accumulator seeds start from the float-bit offset; the V codes add 128 * their sums
+        if (threadIdx.x < nblk * DKP)
+            reinterpret_cast<int *>(imgp(threadIdx.x / DKP) + L::CS_OFF)[threadIdx.x % DKP] = PV_MAGIC_BITS;
         // V: absmax per channel through LDS integer maxima
         if (von) {
             unsigned mb[4] = {0u, 0u, 0u, 0u};
@@ -658,33 +680,26 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
                 if (4 * quad < N && quad < 2 * BV / 4) {
                     unsigned packed[8];
                     quant_quad(vw[kq], &sdelta[0][0][0], srcp, sthr, vc, packed);
-                    char *dstv = imgp(quad / (BV / 4)) + L::V_OFF + 4 * (quad % (BV / 4));
+                    char *imgq = imgp(quad / (BV / 4));
+                    char *dstv = imgq + L::V_OFF + 4 * (quad % (BV / 4));
+                    int *cs = reinterpret_cast<int *>(imgq + L::CS_OFF);
 #pragma unroll
-                    for (int i = 0; i < 8; ++i)
+                    for (int i = 0; i < 8; ++i) {
                         *reinterpret_cast<unsigned *>(dstv + (8 * vc + i) * L::VP) = packed[i];
+                        atomicAdd(&cs[8 * vc + i], 128 * __builtin_amdgcn_sdot4((int)packed[i], 0x01010101, 0, false));
+                    }
                 }
             }
-        }
-        __syncthreads();
-        // accumulator seeds: 128 * column sums + the float-bit offset
-        if (threadIdx.x < nblk * DKP) {
-            const int blk = threadIdx.x / DKP, ch = threadIdx.x % DKP;
-            int sum = 0;
-#pragma unroll
-            for (int j = 0; j < BV / 16; ++j) {
-                const u4 x = *reinterpret_cast<const u4 *>(imgp(blk) + L::V_OFF + ch * L::VP + 16 * j);
-#pragma unroll
-                for (int n = 0; n < 4; ++n) sum = __builtin_amdgcn_sdot4((int)x[n], 0x01010101, sum, false);
-            }
-            reinterpret_cast<int *>(imgp(blk) + L::CS_OFF)[ch] = PV_MAGIC_BITS + 128 * sum;
         }
     } else {
         dma_image<DK>(image_ptr(cur), lds_offset(bufA) + isel * L::BYTES, wave, lane);
         fetch_item_regs(cur);
     }
     begin_item(cur);
-    if (MODE == BIAS_BF16_VEC) load_bias_vec(brow, 0);
-    if (LDS_BIAS) dma_bias(bsrc, 0, lds_offset(bA));
+    if (!ONEHEAD) {
+        if (MODE == BIAS_BF16_VEC) load_bias_vec(brow, 0);
+        if (LDS_BIAS) dma_bias(bsrc, 0, lds_offset(bA));
+    }
     wait_vmem();
     __syncthreads();
 
