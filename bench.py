@@ -201,7 +201,7 @@ def main():
     a = parse()
     if a.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (each (batch, head) problem "
-              "is independent; see DESIGN.md for how it would shard). Run with --gpus 1.", file=sys.stderr)
+              "is independent and would shard over them, or over query rows, with no exchange step). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"

@@ -37,7 +37,7 @@ int check_workspace(const void *ws, size_t bytes, const Workspace &w) {
 
 extern "C" {
 
-int binattn_version(void) { return 100; }
+int binattn_version(void) { return 120; }
 
 const char *binattn_strerror(int code) {
     switch (code) {
