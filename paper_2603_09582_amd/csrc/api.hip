@@ -141,6 +141,7 @@ int attend_impl(const uint32_t *q_bits, const float *mu_q, const float *mu_k, co
     int mode = BIAS_NONE;
     Strides3 bs = {0, 0, 0};
     int gx_shift = 0;
+    bool wide_rows2 = false;
     if (ax != nullptr) {
         if ((rc = check_axial(*ax, N)) != BINATTN_OK) return rc;
         while ((1 << gx_shift) < ax->Gx) ++gx_shift;
@@ -159,7 +160,10 @@ int attend_impl(const uint32_t *q_bits, const float *mu_q, const float *mu_k, co
             // room for two workgroups per CU (d <= 96); everything else takes register loads.
             const bool rows16 = aligned(bias, 16) && bs.b % 8 == 0 && bs.h % 8 == 0 && bs.n % 8 == 0;
             // (and a row pitch whose 7-fold fits a 32-bit lane offset)
-            mode = (rows16 && N % 8 == 0 && s.DK <= 3 && bs.n < (1 << 27)) ? BIAS_BF16_LDS : BIAS_BF16_VEC;
+            // (d > 96 and at least two row blocks: 8-wave workgroups over row-block pairs)
+            const bool lds_ok = rows16 && N % 8 == 0 && bs.n < (1 << 27);
+            wide_rows2 = lds_ok && s.DK == 4 && N > BR && raw == nullptr;
+            mode = (lds_ok && (s.DK <= 3 || wide_rows2)) ? BIAS_BF16_LDS : BIAS_BF16_VEC;
         } else {
             mode = BIAS_F32_VEC;
         }
@@ -194,6 +198,7 @@ int attend_impl(const uint32_t *q_bits, const float *mu_q, const float *mu_k, co
         p.xv = static_cast<const uint16_t *>(raw->v);
         p.xqs = raw->qs; p.xks = raw->ks; p.xvs = raw->vs;
         p.mu_q_out = raw->mu_q_out; p.mu_k_out = raw->mu_k_out;
+        p.wide = 1;
         p.nrb = 1;
         p.nb = 2;
         p.total_wg = B * H;
@@ -208,7 +213,15 @@ int attend_impl(const uint32_t *q_bits, const float *mu_q, const float *mu_k, co
     p.xq = p.xk = p.xv = nullptr;
     p.xqs = p.xks = p.xvs = Strides3{0, 0, 0};
     p.mu_q_out = p.mu_k_out = nullptr;
+    p.wide = 0;
     p.nrb = (N + BR - 1) / BR;
+    if (wide_rows2) {
+        p.wide = 2;
+        p.nb = 2;
+        p.nrb = (p.nrb + 1) / 2;
+        p.total_wg = p.nrb * H * B;
+        return launch_fused_dk<4>(p, mode, st);
+    }
     // Long sequences with a batch-shared, LDS-staged bias: pair batch entries in one
     // workgroup so that the bias stream is fetched once per pair.
     p.nb = (mode == BIAS_BF16_LDS && bs.b == 0 && B % 2 == 0 && s.DK <= 2 && s.nblk >= 8) ? 2 : 1;

@@ -116,15 +116,15 @@ __device__ __forceinline__ void dma16(const void *sbase, unsigned voff, unsigned
 }
 
 // Asynchronous copy of one block image (L::BYTES, a multiple of 1 KiB) from
-// global memory straight into LDS: each of the four waves of a batch entry moves
-// 1 KiB per instruction.
-template <int DK>
+// global memory straight into LDS by NW waves (wave = 0 .. NW - 1), each of
+// which moves 1 KiB per instruction.
+template <int DK, int NW = 4>
 __device__ __forceinline__ void dma_image(const char *__restrict__ gsrc, unsigned ldst, int wave, int lane) {
     using L = Image<DK>;
     constexpr int NCH = L::BYTES / 1024;
 #pragma unroll
-    for (int i = 0; i < (NCH + 3) / 4; ++i) {
-        const int c = wave + 4 * i;
+    for (int i = 0; i < (NCH + NW - 1) / NW; ++i) {
+        const int c = wave + NW * i;
         if (c < NCH) dma16(gsrc + c * 1024, lane * 16, ldst + c * 1024);
     }
 }

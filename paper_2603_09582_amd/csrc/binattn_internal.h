@@ -149,6 +149,7 @@ struct FusedParams {
     const float *delta;
     int B, H, N, d, nblk, nrb, total_wg;
     int nb;              // batch entries per workgroup (1 or 2)
+    int wide;            // 0, or 2: 8-wave workgroups over row-block pairs (nrb counts pairs)
     // single-launch short-sequence kernel: the bf16 inputs, whether mu is applied, optional mu exports
     const uint16_t *xq, *xk, *xv;
     Strides3 xqs, xks, xvs;

@@ -78,13 +78,21 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
 // fused into their consumer), then runs the same block loop on its two 128-row blocks
 // (waves 0-3 / 4-7).  Nothing but the bias and the inputs is read from memory and only the
 // output is written.
-template <int DK, int MODE, int NB, bool ONEHEAD = false>
+//
+// WIDE_ROWS2 (8 waves) serves head dimensions whose operand images leave no LDS room for two
+// 4-wave workgroups with bias tiles (d > 96): the two halves of the workgroup are the row
+// blocks 2 rp, 2 rp + 1 of ONE (batch, head); they share the operand images (one copy stream
+// for 256 rows) and keep private bias tiles; the grid is persistent as with NB = 1.
+enum { WIDE_NONE = 0, WIDE_ONEHEAD = 1, WIDE_ROWS2 = 2 };
+template <int DK, int MODE, int NB, int WIDE = WIDE_NONE>
 __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const FusedParams p) {
     using L = Image<DK>;
-    static_assert(!ONEHEAD || NB == 2, "the single-launch form uses 8 waves");
-    constexpr bool PAIR = NB == 2 && !ONEHEAD;  // two batch entries sharing bias tiles
+    constexpr bool ONEHEAD = WIDE == WIDE_ONEHEAD, ROWS2 = WIDE == WIDE_ROWS2;
+    static_assert(WIDE == WIDE_NONE || NB == 2, "the wide forms use 8 waves");
+    constexpr bool PAIR = NB == 2 && WIDE == WIDE_NONE;  // two batch entries sharing bias tiles
+    constexpr int NWI = ROWS2 ? 8 : 4;                   // waves that copy one operand image
     constexpr int NIMG = PAIR ? 2 : 1;          // operand images per buffer
-    constexpr bool PERSIST = NB == 1;
+    constexpr bool PERSIST = NB == 1 || ROWS2;
     constexpr int DKP = 32 * DK;
     constexpr int DK2 = L::DK2;
     constexpr bool LDS_BIAS = MODE == BIAS_BF16_LDS;
@@ -97,7 +105,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     __shared__ __attribute__((aligned(1024))) char bufB[NIMG * L::BYTES];
     // BIAS_BF16_LDS: staging of the 32 x 128 bias tiles, 8 KiB per 32-row group.
     // NB = 1: one region per wave, private to it.  NB = 2: two buffers shared by the pair.
-    __shared__ __attribute__((aligned(1024))) char biasA[LDS_BIAS ? (ONEHEAD ? 8 : 4) * 8192 : 1024];
+    __shared__ __attribute__((aligned(1024))) char biasA[LDS_BIAS ? (WIDE != WIDE_NONE ? 8 : 4) * 8192 : 1024];
     __shared__ __attribute__((aligned(1024))) char biasB[BIAS_DB ? 4 * 8192 : 1024];
     // BIAS_AXIAL: the head's two relative-position tables, already divided by alpha.
     //   axu: four copies of the REVERSED x table, copy j shifted by j entries, so that every
@@ -117,7 +125,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     const int wave = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) & 3);  // 32-row group
     const int bsel = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);        // half of the workgroup
     const int isel = PAIR ? bsel : 0;                // which resident image / delta copy
-    const int wreg = ONEHEAD ? 4 * bsel + wave : wave;  // this wave's private bias region
+    const int wreg = WIDE != WIDE_NONE ? 4 * bsel + wave : wave;  // this wave's private bias region / copy share
     const int m = lane & 31, g = lane >> 5;
     const int N = p.N, d = p.d, W = (d + 31) / 32;
     const int nbp = p.B / NIMG;
@@ -139,7 +147,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         t.valid = v < vmax && u < p.total_wg;
         const int uu = t.valid ? u : 0;
         t.b = ONEHEAD ? uu / p.H : (uu % nbp) * NIMG + isel;
-        t.rb = ONEHEAD ? bsel : (uu / nbp) % p.nrb;
+        t.rb = ONEHEAD ? bsel : ROWS2 ? 2 * ((uu / nbp) % p.nrb) + bsel : (uu / nbp) % p.nrb;
         t.h = ONEHEAD ? uu % p.H : uu / (nbp * p.nrb);
         t.bh = t.b * p.H + t.h;
         return t;
@@ -377,9 +385,9 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         const char *nimg = sw ? image_ptr(nxt) : imgs + (int64_t)(it + 1) * L::BYTES;
         const int nblkidx = sw ? 0 : it + 1;
         const BiasSrc nsrc = (LDS_BIAS && sw) ? bias_dma_src(nxt) : bsrc;
-        if (!ONEHEAD && more) dma_image<DK>(nimg, inxt + isel * L::BYTES, wave, lane);
+        if (!ONEHEAD && more) dma_image<DK, NWI>(nimg, inxt + isel * L::BYTES, ROWS2 ? wreg : wave, lane);
         if (BIAS_DB && more) dma_bias(nsrc, nblkidx, bnxt);
-        if (!ONEHEAD && it == 0 && wave == 0 && lane < DKP / 4)  // delta_v of this item, for its epilogue
+        if (!ONEHEAD && it == 0 && (ROWS2 ? wreg : wave) == 0 && lane < DKP / 4)  // delta_v of this item, for its epilogue
             dma16(p.delta + (int64_t)cur.bh * DKP, 16 * lane, lds_offset(&sdelta[parity][isel][0]));
         if (sw && nxt.valid) fetch_item_regs(nxt);
 
@@ -692,7 +700,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
             }
         }
     } else {
-        dma_image<DK>(image_ptr(cur), lds_offset(bufA) + isel * L::BYTES, wave, lane);
+        dma_image<DK, NWI>(image_ptr(cur), lds_offset(bufA) + isel * L::BYTES, ROWS2 ? wreg : wave, lane);
         fetch_item_regs(cur);
     }
     begin_item(cur);
@@ -716,6 +724,15 @@ int launch_fused_dk(const FusedParams &p, int mode, hipStream_t stream) {
     // workgroups per CU, 256 CUs), a multiple of 8 so that a workgroup's items stay on one
     // XCD; fewer if there is less work.  NB = 2: one workgroup per item.
     const int needed = ((p.total_wg + 7) / 8) * 8;
+    if (p.wide == WIDE_ROWS2) {  // persistent, one 8-wave workgroup per CU
+        if constexpr (DK == 4) {
+            if (mode != BIAS_BF16_LDS) return BINATTN_ERR_DTYPE;
+            const dim3 grid((unsigned)(needed < 256 ? needed : 256)), block(FUSED_THREADS * 2);
+            hipLaunchKernelGGL((fused_kernel<DK, BIAS_BF16_LDS, 2, WIDE_ROWS2>), grid, block, 0, stream, p);
+            return check_launch();
+        }
+        return BINATTN_ERR_SHAPE;
+    }
     const dim3 grid((unsigned)(p.nb == 2 || needed < 512 ? needed : 512));
     const dim3 block(FUSED_THREADS * p.nb);
     if (p.nb == 2) {
@@ -746,12 +763,12 @@ int launch_onehead_dk(const FusedParams &p, int mode, hipStream_t stream) {
     const int needed = ((p.total_wg + 7) / 8) * 8;
     const dim3 grid((unsigned)needed), block(FUSED_THREADS * 2);
     switch (mode) {
-#define CASE(M) case M: hipLaunchKernelGGL((fused_kernel<DK, M, 2, true>), grid, block, 0, stream, p); break;
+#define CASE(M) case M: hipLaunchKernelGGL((fused_kernel<DK, M, 2, WIDE_ONEHEAD>), grid, block, 0, stream, p); break;
         CASE(BIAS_NONE) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC) CASE(BIAS_AXIAL)
 #undef CASE
         case BIAS_BF16_LDS:
             if constexpr (DK <= 3) {
-                hipLaunchKernelGGL((fused_kernel<DK, BIAS_BF16_LDS, 2, true>), grid, block, 0, stream, p);
+                hipLaunchKernelGGL((fused_kernel<DK, BIAS_BF16_LDS, 2, WIDE_ONEHEAD>), grid, block, 0, stream, p);
                 break;
             }
             return BINATTN_ERR_SHAPE;

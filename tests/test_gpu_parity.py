@@ -48,7 +48,8 @@ def small_inputs(B, H, N, d, seed, extra=""):
 
 SHAPES = [(1, 2, 1, 64), (1, 2, 2, 8), (2, 1, 63, 64), (1, 2, 64, 72), (1, 1, 65, 128), (1, 3, 129, 64),
           (2, 2, 197, 64), (1, 2, 255, 72), (1, 1, 257, 16), (1, 2, 300, 104), (1, 1, 520, 32),
-          (1, 1, 256, 128), (1, 2, 136, 96), (2, 1, 384, 64), (2, 1, 1024, 64), (4, 1, 1160, 32)]
+          (1, 1, 256, 128), (1, 2, 136, 96), (2, 1, 384, 64), (2, 1, 1024, 64), (4, 1, 1160, 32),
+          (1, 2, 520, 128), (3, 1, 1160, 104)]
 
 
 @pytest.mark.parametrize("B,H,N,d", SHAPES)
