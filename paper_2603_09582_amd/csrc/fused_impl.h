@@ -371,6 +371,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
 
     // ---- stream position --------------------------------------------------------
     int it = 0;        // key block inside the current item
+    const bool younger = 2 * blockIdx.x >= gridDim.x;
     int parity = 0;    // items alternate between the two delta_v copies
     Item nxt = decode(PERSIST ? v + gridDim.x : vmax);
 
@@ -391,6 +392,15 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
             dma16(p.delta + (int64_t)cur.bh * DKP, 16 * lane, lds_offset(&sdelta[parity][isel][0]));
         if (sw && nxt.valid) fetch_item_regs(nxt);
 
+        // Two 4-wave workgroups share a CU, and the SIMDs issue the older wave first: the
+        // workgroup dispatched first then runs ~25 % faster than the other and leaves the CU
+        // half empty at the end.  The second half of the grid (dispatched after every CU has
+        // its first workgroup) therefore raises its priority on every other block.  Only a
+        // scheduling hint: results do not depend on it.
+        if (NB == 1) {
+            if (younger && (it & 1)) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
         // 1. all LDS reads of the logit phase go out together: bias tile, key rows
         if (LDS_BIAS) {
             const char *row = bbuf + ((m >> 3) * 2 + g) * 1024 + 128 * ((m & 7) ^ ((m >> 3) & 1));
