@@ -564,7 +564,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         // phi and psi of Alg. 1 for this head, straight into the two LDS images.
         constexpr int NT = FUSED_THREADS * NB;
         __shared__ int sabs[DKP];            // per-channel absmax of V (bit patterns)
-        __shared__ float srcp[DKP], sthr[DKP];
+        __shared__ __attribute__((aligned(16))) float srcp[DKP], sthr[DKP];  // bracketing reciprocals of delta_v
         __shared__ float ssum[2][NT / 64];   // |q| and |k| partial sums per wave
         const int C16 = d / 8, nblk = p.nblk;
         auto imgp = [&](int blk) -> char * { return blk ? bufB : bufA; };
@@ -572,23 +572,60 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         const uint16_t *kb_ = p.xk + (int64_t)cur.b * p.xks.b + (int64_t)cur.h * p.xks.h;
         const uint16_t *vb_ = p.xv + (int64_t)cur.b * p.xvs.b + (int64_t)cur.h * p.xvs.h;
 
+        // Every global load of the head goes out before the first one is used, oldest first in
+        // the order of use: the bias tile, this lane's query chunks, the V rows, the key chunks.
+        if (LDS_BIAS) {
+            bsrc = bias_dma_src(cur);
+            dma_bias(bsrc, 0, lds_offset(bA));
+        }
+        if (MODE == BIAS_BF16_VEC) load_bias_vec(bias_row_ptr(cur), 0);
+        // this lane's query row: the chunks of the sign words its B operand needs (channels
+        // 64 s + 32 g + 8 j); addresses are clamped into the row, unused chunks are skipped below
+        const int qrow = cur.rb * BR + wave * ROWS_PER_WAVE + m;
+        u4 qx[DK2][4];
+#pragma unroll
+        for (int sI = 0; sI < DK2; ++sI)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int c0 = 32 * (2 * sI + g) + 8 * j;
+                qx[sI][j] = *reinterpret_cast<const u4 *>(qb_ + (int64_t)min(qrow, N - 1) * p.xqs.n + (c0 < d ? c0 : 0));
+            }
         // V rows into registers: a thread owns quads of consecutive tokens of one 8-channel
         // chunk; consecutive lanes take consecutive chunks (whole-row loads)
-        const int RT = NT / C16;              // thread groups = token quads per pass (>= 32)
-        const int vc = threadIdx.x % C16, vr = threadIdx.x / C16;
+        // i / C16 for 0 <= i < 2^12 and C16 <= 16 without the integer-division sequence:
+        // (i + 0.5) / C16 is at least 1/32 away from every integer, far more than the error
+        // of the fp32 product
+        const float rc16 = 1.0f / (float)C16;
+        auto div_c16 = [&](int i) { return (int)(((float)i + 0.5f) * rc16); };
+        const int RT = div_c16(NT);           // thread groups = token quads per pass (>= 32)
+        const int vr = div_c16(threadIdx.x), vc = threadIdx.x - vr * C16;
         const bool von = vr < RT;
+        // (loads are unconditional from clamped rows and masked where they are used: a load
+        // under a condition makes the compiler wait for it on the spot)
         u4 vw[2][4];
+        auto v_row_on = [&](int kq, int t) { return von && 4 * (vr + kq * RT) + t < N && vr + kq * RT < 2 * BV / 4; };
 #pragma unroll
         for (int kq = 0; kq < 2; ++kq)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int row = 4 * (vr + kq * RT) + t;
-                vw[kq][t] = u4{0u, 0u, 0u, 0u};
-                if (von && row < N && vr + kq * RT < 2 * BV / 4)
-                    vw[kq][t] = *reinterpret_cast<const u4 *>(vb_ + (int64_t)row * p.xvs.n + 8 * vc);
-            }
-        // this lane's query row: the sign words its B operand needs (channels 64 s + 32 g + ..)
-        const int qrow = cur.rb * BR + wave * ROWS_PER_WAVE + m;
+            for (int t = 0; t < 4; ++t)
+                vw[kq][t] = *reinterpret_cast<const u4 *>(vb_ + (int64_t)min(4 * (vr + kq * RT) + t, N - 1) * p.xvs.n + 8 * vc);
+        // this thread's key chunks (8 channels of one key each), loaded before the first barrier
+        constexpr int KPT = (2 * BV * 4 * DK + NT - 1) / NT;  // chunks per thread, at most
+        u4 kx[KPT];
+#pragma unroll
+        for (int kk = 0; kk < KPT; ++kk) {
+            const int i = threadIdx.x + kk * NT;
+            const int ic = div_c16(i), c8 = i - ic * C16, pos = ic % BV, blk = ic / BV;
+            const int key = blk * BV + key_of_position(pos);
+            kx[kk] = *reinterpret_cast<const u4 *>(kb_ + (int64_t)min(key, N - 1) * p.xks.n + 8 * c8);
+        }
+        // clear both images, the absmax cells
+        for (int i = threadIdx.x; i < L::BYTES / 16; i += NT) {
+            reinterpret_cast<u4 *>(bufA)[i] = u4{0u, 0u, 0u, 0u};
+            reinterpret_cast<u4 *>(bufB)[i] = u4{0u, 0u, 0u, 0u};
+        }
+        if (threadIdx.x < DKP) sabs[threadIdx.x] = 0;
+        // the sign words of the query row (the oldest loads: V and K may still be in flight)
         float qsum = 0.0f;
 #pragma unroll
         for (int w = 0; w < 2 * DK2; ++w) pend_q[w] = 0u;
@@ -596,46 +633,17 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         for (int sI = 0; sI < DK2; ++sI) {
             unsigned word = 0;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int c0 = 32 * (2 * sI + g) + 8 * j;
-                if (qrow < N && c0 < d) {
-                    const u4 x = *reinterpret_cast<const u4 *>(qb_ + (int64_t)qrow * p.xqs.n + c0);
-                    word |= sign_bits8_abs(x, qsum) << (8 * j);
-                }
-            }
+            for (int j = 0; j < 4; ++j)
+                if (qrow < N && 32 * (2 * sI + g) + 8 * j < d) word |= sign_bits8_abs(qx[sI][j], qsum) << (8 * j);
             if (g) pend_q[2 * sI + 1] = word; else pend_q[2 * sI] = word;
         }
-        // this thread's key chunks (8 channels of one key each), loaded before the first barrier
-        constexpr int KPT = (2 * BV * 4 * DK + NT - 1) / NT;  // chunks per thread, at most
-        u4 kx[KPT];
-#pragma unroll
-        for (int kk = 0; kk < KPT; ++kk) {
-            const int i = threadIdx.x + kk * NT;
-            const int c8 = i % C16, pos = (i / C16) % BV, blk = i / (C16 * BV);
-            const int key = blk * BV + key_of_position(pos);
-            kx[kk] = u4{0u, 0u, 0u, 0u};
-            if (blk < nblk && key < N)
-                kx[kk] = *reinterpret_cast<const u4 *>(kb_ + (int64_t)key * p.xks.n + 8 * c8);
-        }
-        // the first bias tile / bias registers do not depend on anything computed here
-        if (LDS_BIAS) {
-            bsrc = bias_dma_src(cur);
-            dma_bias(bsrc, 0, lds_offset(bA));
-        }
-        if (MODE == BIAS_BF16_VEC) load_bias_vec(bias_row_ptr(cur), 0);
-        // clear both images, the absmax cells
-        for (int i = threadIdx.x; i < L::BYTES / 4; i += NT) {
-            reinterpret_cast<unsigned *>(bufA)[i] = 0u;
-            reinterpret_cast<unsigned *>(bufB)[i] = 0u;
-        }
-        if (threadIdx.x < DKP) sabs[threadIdx.x] = 0;
         __syncthreads();
         // keys: sign bits -> FP4 codes of +-1 at the row position the QK tile reads
         float ksum = 0.0f;
 #pragma unroll
         for (int kk = 0; kk < KPT; ++kk) {
             const int i = threadIdx.x + kk * NT;
-            const int c8 = i % C16, pos = (i / C16) % BV, blk = i / (C16 * BV);
+            const int ic = div_c16(i), c8 = i - ic * C16, pos = ic % BV, blk = ic / BV;
             const int key = blk * BV + key_of_position(pos);
             if (blk < nblk && key < N) {
                 const unsigned bits = sign_bits8_abs(kx[kk], ksum);
@@ -653,7 +661,10 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
 #pragma unroll
             for (int kq = 0; kq < 2; ++kq)
 #pragma unroll
-                for (int t = 0; t < 4; ++t) absmax_acc(mb, vw[kq][t]);
+                for (int t = 0; t < 4; ++t) {
+                    if (!v_row_on(kq, t)) vw[kq][t] = u4{0u, 0u, 0u, 0u};  // rows beyond N: code 0
+                    absmax_acc(mb, vw[kq][t]);
+                }
             float mf[8];
             absmax_floats(mb, mf);
 #pragma unroll
@@ -692,12 +703,13 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         __syncthreads();
         // V codes, channel-major, into the images
         if (von) {
+            const QuantConsts8 kc = load_quant_consts8(&sdelta[0][0][0], srcp, sthr, vc);
 #pragma unroll
             for (int kq = 0; kq < 2; ++kq) {
                 const int quad = vr + kq * RT;
                 if (4 * quad < N && quad < 2 * BV / 4) {
                     unsigned packed[8];
-                    quant_quad(vw[kq], &sdelta[0][0][0], srcp, sthr, vc, packed);
+                    quant_quad(vw[kq], kc, packed);
                     char *imgq = imgp(quad / (BV / 4));
                     char *dstv = imgq + L::V_OFF + 4 * (quad % (BV / 4));
                     int *cs = reinterpret_cast<int *>(imgq + L::CS_OFF);

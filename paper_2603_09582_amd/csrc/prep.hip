@@ -114,7 +114,7 @@ __device__ __forceinline__ void quant_v_block(const uint16_t *__restrict__ vb, i
             if (4 * jq + k < nrow)
                 w[k] = *reinterpret_cast<const u4 *>(vb + (int64_t)(j0 + 4 * jq + k) * stride_n + 8 * c);
         }
-        quant_quad(w, sdelta, srcp, sthr, c, packed);
+        quant_quad(w, load_quant_consts8(sdelta, srcp, sthr, c), packed);
         const int col = jq ^ (((c >> 1) & 3) << 3);
 #pragma unroll
         for (int i = 0; i < 8; ++i)
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(
     const uint16_t *__restrict__ v, Strides3 vs, const uint32_t *__restrict__ k_bits, int H, int N,
     int d, int DKP, int nchunk, int nblk, const float *__restrict__ amax, float *__restrict__ delta,
     int img_bytes, int KP, int v_off, int cs_off, char *__restrict__ img) {
-    __shared__ float sdelta[8 * C16], srcp[8 * C16], sthr[8 * C16];
+    __shared__ __attribute__((aligned(16))) float sdelta[8 * C16], srcp[8 * C16], sthr[8 * C16];
     __shared__ __attribute__((aligned(16))) int8_t tile[128 * (BV + 16)];
     const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
     const int b = bh / H, h = bh % H;
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(PREP_THREADS) void prep_head_kernel(
     constexpr int MAXQ = (NQ + RT - 1) / RT;
     constexpr int LDT = BV + 16;            // = Image::VP
     __shared__ float smax[RT * D];
-    __shared__ float sdelta[D], srcp[D], sthr[D];
+    __shared__ __attribute__((aligned(16))) float sdelta[D], srcp[D], sthr[D];
     __shared__ __attribute__((aligned(16))) int8_t tile[2 * 128 * LDT];
     const int bh = blockIdx.x, b = bh / H, h = bh % H;
     const int W = (d + 31) / 32;
@@ -266,12 +266,13 @@ __global__ __launch_bounds__(PREP_THREADS) void prep_head_kernel(
     __syncthreads();
 
     if (on) {
+        const QuantConsts8 kc = load_quant_consts8(sdelta, srcp, sthr, c);
 #pragma unroll
         for (int k = 0; k < MAXQ; ++k) {
             const int quad = r0 + k * RT;
             if (4 * quad < N && quad < NQ) {
                 unsigned packed[8];
-                quant_quad(w[k], sdelta, srcp, sthr, c, packed);
+                quant_quad(w[k], kc, packed);
                 const int blk = quad / (BV / 4), jq = quad % (BV / 4);
                 const int col = jq ^ (((c >> 1) & 3) << 3);  // see quant_v_block
 #pragma unroll

@@ -125,6 +125,35 @@ def test_quant_v_codes_and_delta_exact(B, H, N, d):
             assert np.array_equal(vq[b, h].cpu().numpy(), wq)
 
 
+@pytest.mark.parametrize("N", [97, 256, 700])
+def test_quant_v_ties_and_tiny_channels_exact(N):
+    # Eq. 7 at the quantiser's hard points: quotients exactly on and next to half-integers
+    # (absmax 127 makes delta = 1, absmax 254 delta = 2), a channel of denormal-range values
+    # (1 / delta overflows) and one of huge values.  Codes and scales must equal the oracle's.
+    say(f"quant_v ties N={N}")
+    d = 72
+    g = torch.Generator().manual_seed(900 + N)
+    v = torch.randn(1, 2, N, d, generator=g)
+    half = (torch.randint(-126, 126, (N,), generator=g).float() + 0.5)
+    v[0, :, :, 3] = half                      # delta = 1: every quotient is a tie
+    v[0, :, 0, 3] = 127.0
+    v[0, :, :, 4] = 2.0 * half                # delta = 2: the same ties through a division by 2
+    v[0, :, 0, 4] = -254.0
+    v[0, :, :, 5] = half * (1.0 + 2.0 ** -7)  # bf16 neighbours of the ties
+    v[0, :, 0, 5] = 127.0
+    v[0, :, :, 6] = torch.randn(N, generator=g) * 1e-38   # 127 / absmax is not finite in fp32
+    v[0, :, :, 7] = torch.randn(N, generator=g) * 1e37
+    v[0, 1, :, 8] = 3.0e-39                   # a constant tiny channel: every code is 127
+    v = v.to(torch.bfloat16)
+    vq, delta = ba.quant_v_debug(dev(v))
+    torch.cuda.synchronize()
+    for h in range(2):
+        wq, wd = orc.quant_v(np_bits(v[0, h]))
+        assert np.array_equal(delta[0, h].cpu().numpy(), wd)
+        assert np.array_equal(vq[0, h].cpu().numpy(), wq)
+    assert set(np.unique(vq[0, 0, 1:, 3].cpu().numpy()) % 2) == {0}  # ties went to even codes
+
+
 @pytest.mark.parametrize("variant", [ba.LOGITS_POPCOUNT, ba.LOGITS_MFMA_I8, ba.LOGITS_MFMA_FP4])
 @pytest.mark.parametrize("B,H,N,d", SHAPES)
 def test_integer_logits_exact(B, H, N, d, variant):
@@ -537,6 +566,28 @@ def test_forward_fused_workload_dit_xl2_256_sampled_heads():
         o = orc.attention_rows(q, k, v, np_bits(x.bias[h].cpu()), x.scale, orc.abs_mean(q), orc.abs_mean(k),
                                vq, delta, want=("O2",))
         check_close(gpu_out_f64(out[b, h]), o["O2"], f"dit_xl2_256 head {(b, h)} vs O2")
+
+
+@pytest.mark.parametrize("layout", ["contiguous", "token_major"])
+def test_forward_fused_more_heads_than_cus(layout):
+    # more heads than the chip has CUs: the first workgroups also touch the rows of a later
+    # head (a cache hint); sampled heads against the oracle, every head against the three-call path
+    B, H, N, d = 3, 100, 160, 72
+    say(f"single-launch forward, {B * H} heads, {layout}")
+    x = small_inputs(B, H, N, d, 4242)
+    q, k, v = dev(x.q), dev(x.k), dev(x.v)
+    if layout == "token_major":                  # [B, N, H, d] storage seen as [B, H, N, d]
+        q, k, v = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (q, k, v))
+    out = ba.forward_fused(q, k, v, dev(x.bias), x.scale)
+    torch.cuda.synchronize()
+    got = gpu_out_f64(out)
+    for (b, h) in [(0, 0), (0, 43), (1, 99), (2, 55), (2, 99)]:
+        qq, kk, vv = (np_bits(t[b, h]) for t in (x.q, x.k, x.v))
+        vq, delta = orc.quant_v(vv)
+        o = orc.attention_rows(qq, kk, vv, np_bits(x.bias[h]), x.scale, orc.abs_mean(qq), orc.abs_mean(kk),
+                               vq, delta, want=("O2",))
+        check_close(got[b, h], o["O2"], f"head {(b, h)} vs O2")
+    assert np.abs(got - run_forward(x, x.bias)).max() <= 2e-3
 
 
 # ---- the five workloads ----------------------------------------------------------
