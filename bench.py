@@ -57,6 +57,8 @@ def parse():
     ap.add_argument("--others", action="store_true", help="also time the other workloads (extra field)")
     ap.add_argument("--axial", action="store_true",
                     help="also time the workload with the in-kernel decomposed relative-position bias (extra field)")
+    ap.add_argument("--relpos", action="store_true",
+                    help="also time the DiT workloads with the in-kernel relative-position table (extra field)")
     ap.add_argument("--sweep", choices=["hd128"], help="also time the head-dim-128 sequence-length sweep (extra field)")
     ap.add_argument("--sweep-bias", action="store_true", help="run the sweep with a dense bias (up to N = 16384)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -74,13 +76,21 @@ def axial_grid(N):
     return (N // gx, gx) if N % gx == 0 and N // gx <= 256 else None
 
 
-def run_workload(name, steps, warmup, with_bias=True, axial=False):
+def relpos_grid(N):
+    """Gy, Gx with Gy * Gx = N, Gx in {16, 32} and Gy <= 32 (the limits of binattn_attend_relpos)."""
+    for gx in (32, 16):
+        if N % gx == 0 and N // gx <= 32 and (gx == 16 or N // gx >= 16):
+            return N // gx, gx
+    return None
+
+
+def run_workload(name, steps, warmup, with_bias=True, axial=False, relpos=False):
     import torch
     from paper_2603_09582_amd import binding as ba
     from paper_2603_09582_amd import workloads as wl
 
     w = wl.WORKLOADS[name]
-    x = wl.make_inputs(w, device="cuda", with_bias=with_bias and not axial)
+    x = wl.make_inputs(w, device="cuda", with_bias=with_bias and not axial and not relpos)
     B, H, N, d = w.B, w.H, w.N, w.d
     W = (d + 31) // 32
     dev = x.q.device
@@ -97,6 +107,11 @@ def run_workload(name, steps, warmup, with_bias=True, axial=False):
         by = torch.randn(H, 2 * Gy - 1, generator=gen, device=dev) * 0.02
         bx = torch.randn(H, 2 * Gx - 1, generator=gen, device=dev) * 0.02
 
+    if relpos:  # the full relative-position table of each head instead of [H, N, N]
+        Gy, Gx = relpos_grid(N)
+        gen = torch.Generator(device="cuda").manual_seed(w.seed + 2000)
+        table = torch.randn(H, 2 * Gy - 1, 2 * Gx - 1, generator=gen, device=dev) * 0.02
+
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
 
     def step(e=None):
@@ -107,6 +122,8 @@ def run_workload(name, steps, warmup, with_bias=True, axial=False):
         if e: e[2].record()
         if axial:
             ba.attend_axial(q_bits, mu_q, mu_k, by, bx, x.scale, d, ws, out=out)
+        elif relpos:
+            ba.attend_relpos(q_bits, mu_q, mu_k, table, x.scale, d, ws, out=out)
         else:
             ba.attend(q_bits, mu_q, mu_k, x.bias, x.scale, d, ws, out=out)
         if e: e[3].record()
@@ -139,7 +156,7 @@ def run_workload(name, steps, warmup, with_bias=True, axial=False):
         "fused_hbm_bytes": 2 * H * N * N + B * H * N * (W * 4 + 2 * 32 * W + 2 * d),
     }
     res["fused_hbm_gbs"] = res["fused_hbm_bytes"] / (fused_ms * 1e-3) / 1e9
-    if N <= 256 and not axial:  # the single-launch form of the same step (binattn_forward_fused)
+    if N <= 256 and not axial and not relpos:  # the single-launch form of the same step (binattn_forward_fused)
         for _ in range(warmup):
             ba.forward_fused(x.q, x.k, x.v, x.bias, x.scale, out=out)
         torch.cuda.synchronize()
@@ -255,6 +272,21 @@ def main():
         line["axial_bias"] = {"grid": [Gy, Gx], "ms_per_step": r["ms_per_step"], "attend_ms": r["fused_ms"],
                               "tops_equiv": r["tops_equiv"], "fused_kernel_tops_equiv": r["fused_tops_equiv"],
                               "note": "b_ij = y[iy-jy] + x[ix-jx] from two fp32 tables per head held in LDS"}
+        _, x = run_workload(a.workload, 1, 0)
+    if a.relpos:
+        del x
+        torch.cuda.empty_cache()
+        rows = []
+        for name in ("dit_xl2_256", "dit_xl2_512"):
+            r, xr = run_workload(name, max(5, a.steps), a.warmup, relpos=True)
+            del xr
+            torch.cuda.empty_cache()
+            rows.append({"workload": name, "grid": list(relpos_grid(r["N"])), "ms_per_step": r["ms_per_step"],
+                         "attend_ms": r["fused_ms"], "tops_equiv": r["tops_equiv"],
+                         "fused_kernel_tops_equiv": r["fused_tops_equiv"],
+                         "alu_frac": r["alu_tlaneops"] / ALU_PEAK_TLANEOPS})
+        line["relpos_table_bias"] = {"note": "b_ij = table[iy-jy][ix-jx], the head's fp32 table held in LDS",
+                                     "workloads": rows}
         _, x = run_workload(a.workload, 1, 0)
     if a.sweep:
         del x

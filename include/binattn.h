@@ -126,10 +126,10 @@ int binattn_attend(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
 
 /*
  * binattn_attend with a DECOMPOSED relative-position bias generated inside the kernel
- * instead of a dense [N, N] matrix (Sec. 4.2: the bias "can be instantiated as
- * position-sensitive"; Sec. 5.4 memory study: "a decomposable bias, e.g. a sum over spatial
- * directions", whose memory overhead is negligible).  Tokens form a Gy x Gx grid in
- * row-major order, n = iy * Gx + ix, with Gy * Gx = N, and
+ * instead of a dense [N, N] matrix.  Sec. 4.2 allows the bias of Eq. 6 to depend on position
+ * only, and the memory study of the ablations (Sec. 5.6) points to a bias that splits into a
+ * sum over the spatial directions as the way to avoid the dense matrix's footprint.  Tokens
+ * form a Gy x Gx grid in row-major order, n = iy * Gx + ix, with Gy * Gx = N, and
  *     b_ij = bias_y[h][iy - jy + Gy - 1] + bias_x[h][ix - jx + Gx - 1].
  *   bias_y : float32 [H, 2 Gy - 1] contiguous, shared over the batch.
  *   bias_x : float32 [H, 2 Gx - 1] contiguous.
@@ -140,6 +140,21 @@ int binattn_attend_axial(const uint32_t *q_bits, const float *mu_q, const float 
                          const float *bias_y, const float *bias_x, int Gy, int Gx, float scale, int B,
                          int H, int N, int d, void *out, const int64_t out_strides[3],
                          const void *workspace, size_t workspace_bytes, unsigned flags, void *stream);
+
+/*
+ * binattn_attend with the full learnable relative-position table as bias (the bias the
+ * ablations of Sec. 5.6 train), generated inside the kernel: tokens form a Gy x Gx grid in
+ * row-major order, n = iy * Gx + ix, with Gy * Gx = N, and
+ *     b_ij = table[h][iy - jy + Gy - 1][ix - jx + Gx - 1].
+ *   table : float32 [H, 2 Gy - 1, 2 Gx - 1] contiguous, shared over the batch, finite values.
+ *   Gx    : 16 or 32;  Gy in [1, 32]  (BINATTN_ERR_SHAPE otherwise: the head's table is
+ *           held in LDS; larger grids take the dense or the decomposed form).
+ * Everything else as binattn_attend; BINATTN_FLAG_NO_BIAS ignores the table.
+ */
+int binattn_attend_relpos(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
+                          const float *table, int Gy, int Gx, float scale, int B, int H, int N, int d,
+                          void *out, const int64_t out_strides[3], const void *workspace,
+                          size_t workspace_bytes, unsigned flags, void *stream);
 
 /*
  * binattn_prepare_kv followed by binattn_attend (all of Alg. 1 after phi);
@@ -158,6 +173,13 @@ int binattn_forward_axial(const uint32_t *q_bits, const uint32_t *k_bits, const 
                           const float *bias_y, const float *bias_x, int Gy, int Gx, float scale, int B,
                           int H, int N, int d, void *out, const int64_t out_strides[3], void *workspace,
                           size_t workspace_bytes, unsigned flags, void *stream);
+
+/* binattn_prepare_kv followed by binattn_attend_relpos. */
+int binattn_forward_relpos(const uint32_t *q_bits, const uint32_t *k_bits, const float *mu_q,
+                           const float *mu_k, const void *v, const int64_t v_strides[3],
+                           const float *table, int Gy, int Gx, float scale, int B, int H, int N, int d,
+                           void *out, const int64_t out_strides[3], void *workspace,
+                           size_t workspace_bytes, unsigned flags, void *stream);
 
 /*
  * All of Alg. 1 in ONE launch for short sequences (N <= 256): phi (Eq. 5: sign bits and

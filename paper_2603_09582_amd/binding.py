@@ -21,7 +21,8 @@ LOGITS_POPCOUNT, LOGITS_MFMA_I8, LOGITS_MFMA_FP4 = 0, 1, 2
 
 EXPORTS = ["binattn_version", "binattn_strerror", "binattn_pack_qk", "binattn_workspace_bytes",
            "binattn_prepare_kv", "binattn_attend", "binattn_forward", "binattn_attend_axial",
-           "binattn_forward_axial", "binattn_forward_fused", "binattn_logits_debug", "binattn_quant_v_debug"]
+           "binattn_forward_axial", "binattn_attend_relpos", "binattn_forward_relpos", "binattn_forward_fused",
+           "binattn_logits_debug", "binattn_quant_v_debug"]
 
 _lib = None
 
@@ -69,6 +70,13 @@ def lib():
     L.binattn_forward_axial.argtypes = [vp, vp, vp, vp, vp, i64p, vp, vp, C.c_int, C.c_int, C.c_float,
                                         C.c_int, C.c_int, C.c_int, C.c_int, vp, i64p, vp, C.c_size_t,
                                         C.c_uint, vp]
+    L.binattn_attend_relpos.restype = C.c_int
+    L.binattn_attend_relpos.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.c_float, C.c_int, C.c_int,
+                                        C.c_int, C.c_int, vp, i64p, vp, C.c_size_t, C.c_uint, vp]
+    L.binattn_forward_relpos.restype = C.c_int
+    L.binattn_forward_relpos.argtypes = [vp, vp, vp, vp, vp, i64p, vp, C.c_int, C.c_int, C.c_float,
+                                         C.c_int, C.c_int, C.c_int, C.c_int, vp, i64p, vp, C.c_size_t,
+                                         C.c_uint, vp]
     L.binattn_forward_fused.restype = C.c_int
     L.binattn_forward_fused.argtypes = [vp, vp, vp, i64p, i64p, i64p, vp, C.c_int, i64p, C.c_float, C.c_int,
                                         C.c_int, C.c_int, C.c_int, vp, i64p, vp, vp, C.c_uint, vp]
@@ -207,6 +215,47 @@ def forward_axial(q_bits: torch.Tensor, k_bits: torch.Tensor, mu_q: Optional[tor
         bias_x.data_ptr(), Gy, Gx, float(scale), B, H, N, d, out.data_ptr(), _strides3(out),
         workspace.data_ptr(), workspace.numel(), int(flags), _stream())
     _check(rc, "binattn_forward_axial")
+    return out
+
+
+def _relpos_table(table: torch.Tensor, H: int):
+    assert table.dtype == torch.float32 and table.is_contiguous() and table.dim() == 3 and table.shape[0] == H
+    return (table.shape[1] + 1) // 2, (table.shape[2] + 1) // 2
+
+
+def attend_relpos(q_bits: torch.Tensor, mu_q: Optional[torch.Tensor], mu_k: Optional[torch.Tensor],
+                  table: torch.Tensor, scale: float, d: int, workspace: torch.Tensor,
+                  out: Optional[torch.Tensor] = None, flags: int = 0) -> torch.Tensor:
+    """binattn_attend_relpos: table fp32 [H, 2Gy-1, 2Gx-1]; N = Gy * Gx."""
+    B, H, N, _ = q_bits.shape
+    Gy, Gx = _relpos_table(table, H)
+    if out is None:
+        out = torch.empty(B, H, N, d, dtype=torch.bfloat16, device=q_bits.device)
+    rc = lib().binattn_attend_relpos(
+        q_bits.data_ptr(), None if mu_q is None else mu_q.data_ptr(),
+        None if mu_k is None else mu_k.data_ptr(), table.data_ptr(), Gy, Gx, float(scale), B, H, N, d,
+        out.data_ptr(), _strides3(out), workspace.data_ptr(), workspace.numel(), int(flags), _stream())
+    _check(rc, "binattn_attend_relpos")
+    return out
+
+
+def forward_relpos(q_bits: torch.Tensor, k_bits: torch.Tensor, mu_q: Optional[torch.Tensor],
+                   mu_k: Optional[torch.Tensor], v: torch.Tensor, table: torch.Tensor, scale: float,
+                   out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                   flags: int = 0) -> torch.Tensor:
+    """binattn_forward_relpos = prepare_kv + attend_relpos."""
+    B, H, N, d = v.shape
+    Gy, Gx = _relpos_table(table, H)
+    if out is None:
+        out = torch.empty(B, H, N, d, dtype=torch.bfloat16, device=v.device)
+    if workspace is None:
+        workspace = alloc_workspace(B, H, N, d, v.device)
+    rc = lib().binattn_forward_relpos(
+        q_bits.data_ptr(), k_bits.data_ptr(), None if mu_q is None else mu_q.data_ptr(),
+        None if mu_k is None else mu_k.data_ptr(), v.data_ptr(), _strides3(v), table.data_ptr(), Gy, Gx,
+        float(scale), B, H, N, d, out.data_ptr(), _strides3(out), workspace.data_ptr(),
+        workspace.numel(), int(flags), _stream())
+    _check(rc, "binattn_forward_relpos")
     return out
 
 

@@ -37,7 +37,7 @@ int check_workspace(const void *ws, size_t bytes, const Workspace &w) {
 
 extern "C" {
 
-int binattn_version(void) { return 120; }
+int binattn_version(void) { return 130; }
 
 const char *binattn_strerror(int code) {
     switch (code) {
@@ -97,9 +97,12 @@ int binattn_prepare_kv(const uint32_t *k_bits, const void *v, const int64_t v_st
 
 namespace {
 
+// bias generated in the kernel from relative positions on a Gy x Gx token grid: either the
+// two tables of the decomposed form (y, x) or the full table (table)
 struct AxialBias {
     const float *y, *x;
     int Gy, Gx;
+    const float *table = nullptr;
 };
 
 // inputs of the single-launch form (binattn_forward_fused)
@@ -111,12 +114,15 @@ struct RawInputs {
 
 // BIAS_AXIAL arguments: tables present and aligned, Gx a power of two in [16, 256],
 // Gy in [1, 256], Gy * Gx = N.
+// BIAS_TABLE: table present and aligned, Gx a power of two in [16, 32], Gy in [1, 32].
 int check_axial(const AxialBias &ax, int N) {
-    if (!ax.y || !ax.x) return BINATTN_ERR_NULL;
-    if (ax.Gy < 1 || ax.Gy > AXIAL_MAX_G || ax.Gx < 16 || ax.Gx > AXIAL_MAX_G ||
+    const bool full = ax.table != nullptr;
+    if (!full && (!ax.y || !ax.x)) return BINATTN_ERR_NULL;
+    const int gmax = full ? TABLE_MAX_G : AXIAL_MAX_G;
+    if (ax.Gy < 1 || ax.Gy > gmax || ax.Gx < 16 || ax.Gx > gmax ||
         (ax.Gx & (ax.Gx - 1)) != 0 || (int64_t)ax.Gy * ax.Gx != N)
         return BINATTN_ERR_SHAPE;
-    if (!aligned(ax.y, 4) || !aligned(ax.x, 4)) return BINATTN_ERR_ALIGN;
+    if (full ? !aligned(ax.table, 4) : (!aligned(ax.y, 4) || !aligned(ax.x, 4))) return BINATTN_ERR_ALIGN;
     return BINATTN_OK;
 }
 
@@ -145,7 +151,7 @@ int attend_impl(const uint32_t *q_bits, const float *mu_q, const float *mu_k, co
     if (ax != nullptr) {
         if ((rc = check_axial(*ax, N)) != BINATTN_OK) return rc;
         while ((1 << gx_shift) < ax->Gx) ++gx_shift;
-        if (!no_bias) mode = BIAS_AXIAL;
+        if (!no_bias) mode = ax->table ? BIAS_TABLE : BIAS_AXIAL;
     } else if (use_bias) {
         if (bias_dtype != BINATTN_BIAS_BF16 && bias_dtype != BINATTN_BIAS_F32) return BINATTN_ERR_DTYPE;
         if (!bias_strides) return BINATTN_ERR_NULL;
@@ -188,6 +194,7 @@ int attend_impl(const uint32_t *q_bits, const float *mu_q, const float *mu_k, co
     p.nblk = s.nblk;
     p.ax_y = ax ? ax->y : nullptr;
     p.ax_x = ax ? ax->x : nullptr;
+    p.table = ax ? ax->table : nullptr;
     p.Gy = ax ? ax->Gy : 0;
     p.Gx = ax ? ax->Gx : 0;
     p.gx_shift = gx_shift;
@@ -256,6 +263,17 @@ int binattn_attend_axial(const uint32_t *q_bits, const float *mu_q, const float 
                        out_strides, workspace, workspace_bytes, flags, stream);
 }
 
+int binattn_attend_relpos(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
+                          const float *table, int Gy, int Gx, float scale, int B, int H, int N, int d,
+                          void *out, const int64_t out_strides[3], const void *workspace,
+                          size_t workspace_bytes, unsigned flags, void *stream) {
+    if (!table) return BINATTN_ERR_NULL;
+    AxialBias ax = {nullptr, nullptr, Gy, Gx};
+    ax.table = table;
+    return attend_impl(q_bits, mu_q, mu_k, nullptr, 0, nullptr, &ax, nullptr, scale, B, H, N, d, out,
+                       out_strides, workspace, workspace_bytes, flags, stream);
+}
+
 int binattn_forward(const uint32_t *q_bits, const uint32_t *k_bits, const float *mu_q,
                     const float *mu_k, const void *v, const int64_t v_strides[3], const void *bias,
                     int bias_dtype, const int64_t bias_strides[3], float scale, int B, int H, int N,
@@ -310,6 +328,32 @@ int binattn_forward_axial(const uint32_t *q_bits, const uint32_t *k_bits, const 
         return rc;
     return binattn_attend_axial(q_bits, mu_q, mu_k, bias_y, bias_x, Gy, Gx, scale, B, H, N, d, out,
                                 out_strides, workspace, workspace_bytes, flags, stream);
+}
+
+int binattn_forward_relpos(const uint32_t *q_bits, const uint32_t *k_bits, const float *mu_q,
+                           const float *mu_k, const void *v, const int64_t v_strides[3],
+                           const float *table, int Gy, int Gx, float scale, int B, int H, int N, int d,
+                           void *out, const int64_t out_strides[3], void *workspace,
+                           size_t workspace_bytes, unsigned flags, void *stream) {
+    // Validate the second stage's arguments before the first stage launches anything.
+    if (!q_bits || !k_bits || !v || !out || !table) return BINATTN_ERR_NULL;
+    if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
+    const Shape s = make_shape(B, H, N, d);
+    Strides3 tmp;
+    int rc;
+    if ((rc = check_strides_bhnd(v_strides, s, &tmp)) != BINATTN_OK) return rc;
+    if ((rc = check_strides_bhnd(out_strides, s, &tmp)) != BINATTN_OK) return rc;
+    if (!aligned(v, 16) || !aligned(out, 16) || !aligned(q_bits, 4) || !aligned(k_bits, 4))
+        return BINATTN_ERR_ALIGN;
+    if ((mu_q && !aligned(mu_q, 4)) || (mu_k && !aligned(mu_k, 4))) return BINATTN_ERR_ALIGN;
+    AxialBias ax = {nullptr, nullptr, Gy, Gx};
+    ax.table = table;
+    if ((rc = check_axial(ax, N)) != BINATTN_OK) return rc;
+    if ((rc = binattn_prepare_kv(k_bits, v, v_strides, B, H, N, d, workspace, workspace_bytes,
+                                 stream)) != BINATTN_OK)
+        return rc;
+    return binattn_attend_relpos(q_bits, mu_q, mu_k, table, Gy, Gx, scale, B, H, N, d, out, out_strides,
+                                 workspace, workspace_bytes, flags, stream);
 }
 
 int binattn_forward_fused(const void *q, const void *k, const void *v, const int64_t q_strides[3],

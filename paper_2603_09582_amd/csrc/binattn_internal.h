@@ -131,11 +131,14 @@ enum BiasMode {
     BIAS_BF16_VEC = 1,  // any element-aligned rows: 16-byte loads into registers, one block ahead
     BIAS_F32_VEC = 3,   // fp32 bias, 16-byte loads at use
     BIAS_BF16_LDS = 5,  // rows 16-byte aligned, N % 8 == 0: tile staged global -> LDS asynchronously
-    BIAS_AXIAL = 7      // b_ij = y[iy - jy] + x[ix - jx] on a Gy x Gx token grid, tables held in LDS
+    BIAS_AXIAL = 7,     // b_ij = y[iy - jy] + x[ix - jx] on a Gy x Gx token grid, tables held in LDS
+    BIAS_TABLE = 9      // b_ij = t[iy - jy][ix - jx]: the full relative-position table of the head in LDS
 };
 
 // largest grid side of BIAS_AXIAL (the tables of one head live in LDS)
 constexpr int AXIAL_MAX_G = 256;
+// largest grid side of BIAS_TABLE ((2 G - 1)^2 entries per head)
+constexpr int TABLE_MAX_G = 32;
 
 struct FusedParams {
     const uint32_t *q_bits;
@@ -156,7 +159,8 @@ struct FusedParams {
     int use_mu;
     float *mu_q_out, *mu_k_out;
     const float *ax_y, *ax_x;  // BIAS_AXIAL: fp32 [H][2 Gy - 1], [H][2 Gx - 1]
-    int Gy, Gx, gx_shift;      // BIAS_AXIAL: token grid, Gx = 1 << gx_shift
+    const float *table;        // BIAS_TABLE: fp32 [H][2 Gy - 1][2 Gx - 1]
+    int Gy, Gx, gx_shift;      // BIAS_AXIAL / BIAS_TABLE: token grid, Gx = 1 << gx_shift
 };
 
 // Defined (and explicitly instantiated) in fused_dk<DK>.hip, DK = ceil(d / 32).

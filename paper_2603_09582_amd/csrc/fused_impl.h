@@ -118,6 +118,14 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     constexpr int AXL = 2 * AXIAL_MAX_G + 16;  // pitch of a copy, in entries
     __shared__ __attribute__((aligned(16))) float axu[AXIAL ? 4 * AXL : 4];
     __shared__ float axw[AXIAL ? AXL : 4];
+    // BIAS_TABLE: the head's (2 Gy - 1) x (2 Gx - 1) table divided by alpha, every row reversed
+    // in x (a lane's 16-entry window then ascends with the key index) at a pitch of TBP
+    // entries.  Windows start at any entry, so they are read entry by entry; the 32 lanes of a
+    // row group read 32 consecutive entries per access (or two runs 16 banks apart when the
+    // group spans two grid rows).
+    constexpr bool TABLE = MODE == BIAS_TABLE;
+    constexpr int TBP = 2 * TABLE_MAX_G + 16;
+    __shared__ float tab2[TABLE ? (2 * TABLE_MAX_G - 1) * TBP : 4];
     // delta_v of the current item (two copies: consecutive items alternate)
     __shared__ __attribute__((aligned(16))) float sdelta[2][NIMG][DKP];
 
@@ -257,6 +265,19 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
             const int s0 = p.Gx - 1 - ix;  // reversed-table index of key column 0
             ax_ub = (s0 & 3) * AXL + (s0 & ~3);
             ax_wb = iy + p.Gy - 1;
+            __syncthreads();
+        }
+        if (TABLE) {
+            // (as above: the previous item's last block is behind every wave)
+            const int LX = 2 * p.Gx - 1, LY = 2 * p.Gy - 1;
+            const float *tb = p.table + (int64_t)t.h * LY * LX;
+            for (int i = threadIdx.x; i < LY * TBP; i += FUSED_THREADS * NB) {
+                const int ry = i / TBP, kk = i % TBP;
+                tab2[i] = kk < LX ? tb[ry * LX + (LX - 1 - kk)] * inv_alpha : 0.0f;
+            }
+            const int qc = min(q, N - 1);
+            ax_ub = p.Gx - 1 - (qc & (p.Gx - 1));       // reversed-row index of key column 0
+            ax_wb = (qc >> p.gx_shift) + p.Gy - 1;      // table row of key row 0
             __syncthreads();
         }
         m_run = -INFINITY;
@@ -427,6 +448,18 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
                     cin[4 * i] = x[0]; cin[4 * i + 1] = x[1]; cin[4 * i + 2] = x[2]; cin[4 * i + 3] = x[3];
                 }
                 wt[t] = axw[ax_wb - jy];
+                T[t] = qk_mfma<DK2>(ka[t], qB, cin);
+            }
+        } else if (TABLE) {
+#pragma unroll
+            for (int t = 0; t < KT; ++t) {
+                const int key0 = it * BV + 64 * g + 16 * t;  // 16 keys of one grid row (Gx >= 16)
+                const int jx0 = key0 & (p.Gx - 1), jy = min(key0 >> p.gx_shift, p.Gy - 1);
+                const float *win = tab2 + (ax_wb - jy) * TBP + ax_ub + jx0;
+                v16f cin;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) cin[r] = win[r];
+                wt[t] = 0.0f;
                 T[t] = qk_mfma<DK2>(ka[t], qB, cin);
             }
         } else {
@@ -767,7 +800,7 @@ int launch_fused_dk(const FusedParams &p, int mode, hipStream_t stream) {
     }
     switch (mode) {
 #define CASE(M) case M: hipLaunchKernelGGL((fused_kernel<DK, M, 1>), grid, block, 0, stream, p); break;
-        CASE(BIAS_NONE) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC) CASE(BIAS_AXIAL)
+        CASE(BIAS_NONE) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC) CASE(BIAS_AXIAL) CASE(BIAS_TABLE)
 #undef CASE
         case BIAS_BF16_LDS:
             if constexpr (DK <= 3) {
@@ -786,7 +819,7 @@ int launch_onehead_dk(const FusedParams &p, int mode, hipStream_t stream) {
     const dim3 grid((unsigned)needed), block(FUSED_THREADS * 2);
     switch (mode) {
 #define CASE(M) case M: hipLaunchKernelGGL((fused_kernel<DK, M, 2, WIDE_ONEHEAD>), grid, block, 0, stream, p); break;
-        CASE(BIAS_NONE) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC) CASE(BIAS_AXIAL)
+        CASE(BIAS_NONE) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC) CASE(BIAS_AXIAL) CASE(BIAS_TABLE)
 #undef CASE
         case BIAS_BF16_LDS:
             if constexpr (DK <= 3) {

@@ -113,6 +113,30 @@ def test_forward_axial_rejects_bad_arguments():
                                   1 << 30, 0, None) == -1
 
 
+def fwd_relpos(table=FAKE, Gy=16, Gx=16, N=256, d=64, qb=FAKE, v=FAKE, out=FAKE, ws=FAKE, wsb=1 << 30, flags=0):
+    B, H = 1, 2
+    s3 = st(H * N * d, N * d, d)
+    return ba.lib().binattn_forward_relpos(qb, FAKE, FAKE, FAKE, v, s3, table, Gy, Gx, 0.125, B, H, N, d, out,
+                                           s3, ws, wsb, flags, None)
+
+
+def test_forward_relpos_rejects_bad_arguments():
+    assert fwd_relpos(table=None) == -1 and fwd_relpos(qb=None) == -1 and fwd_relpos(v=None) == -1
+    assert fwd_relpos(Gx=24, Gy=16, N=384) == -2     # Gx not a power of two
+    assert fwd_relpos(Gx=8, Gy=32) == -2             # Gx below 16
+    assert fwd_relpos(Gx=64, Gy=4) == -2             # Gx above 32
+    assert fwd_relpos(Gx=16, Gy=33, N=16 * 33) == -2 # Gy above 32
+    assert fwd_relpos(Gx=16, Gy=15) == -2            # Gy * Gx != N
+    assert fwd_relpos(table=FAKE + 2) == -4
+    assert fwd_relpos(wsb=100) == -5
+    L = ba.lib()
+    s3 = st(2 * 256 * 64, 256 * 64, 64)
+    assert L.binattn_attend_relpos(FAKE, FAKE, FAKE, FAKE, 16, 16, 0.125, 1, 2, 256, 64, FAKE, s3, FAKE, 100, 0,
+                                   None) == -5
+    assert L.binattn_attend_relpos(FAKE, FAKE, FAKE, None, 16, 16, 0.125, 1, 2, 256, 64, FAKE, s3, FAKE, 1 << 30,
+                                   0, None) == -1
+
+
 def fused(q=FAKE, k=FAKE, v=FAKE, out=FAKE, N=200, d=64, bias=FAKE, bdt=1, bs=None, qs=None, mq=FAKE, flags=0):
     B, H = 2, 2
     s3 = st(H * N * d, N * d, d)

@@ -446,6 +446,72 @@ def test_axial_bias_matches_dense_oracle(B, H, Gy, Gx, d):
     assert torch.equal(a, b)
 
 
+# ---- full relative-position table generated in the kernel -------------------------------
+def relpos_dense(table, Gy, Gx):
+    """The dense [H, N, N] bias the table stands for: b_ij = table[iy-jy+Gy-1][ix-jx+Gx-1]."""
+    n = torch.arange(Gy * Gx)
+    iy, ix = n // Gx, n % Gx
+    dy = iy[:, None] - iy[None, :] + Gy - 1
+    dx = ix[:, None] - ix[None, :] + Gx - 1
+    return table[:, dy, dx]
+
+
+@pytest.mark.parametrize("B,H,Gy,Gx,d", [(2, 2, 16, 16, 72), (1, 2, 32, 32, 72), (1, 2, 5, 32, 64),
+                                         (1, 1, 7, 16, 128), (2, 1, 1, 16, 8), (1, 3, 31, 32, 96)])
+def test_relpos_table_matches_dense_oracle(B, H, Gy, Gx, d):
+    N = Gy * Gx
+    say(f"relative-position table B={B} H={H} grid {Gy}x{Gx} d={d}")
+    x = small_inputs(B, H, N, d, 600 + Gy)
+    g = torch.Generator().manual_seed(Gy * 100 + Gx)
+    table = torch.randn(H, 2 * Gy - 1, 2 * Gx - 1, generator=g) * 0.7
+    dense = relpos_dense(table, Gy, Gx)                        # fp32 [H, N, N]
+    q, k, v = dev(x.q), dev(x.k), dev(x.v)
+    qb, kb, mq, mk = ba.pack_qk(q, k)
+    out = ba.forward_relpos(qb, kb, mq, mk, v, dev(table), x.scale)
+    torch.cuda.synchronize()
+    got = gpu_out_f64(out)
+    ref = oracle_algorithm1(x, dense, Bv=128)
+    err = np.abs(got - ref)
+    say(f"    vs Alg.1(Bv=128): max abs err {err.max():.3e}")
+    assert np.all(err <= 2e-3 + 2 ** -7 * np.abs(ref))
+    check_close(got, oracle_forward(x, dense)["O2"], "relpos: out vs O2 (dense oracle)")
+    # and against the library's own dense path on the same bias
+    out_dense = ba.forward(qb, kb, mq, mk, v, dev(dense), x.scale)
+    torch.cuda.synchronize()
+    diff = np.abs(got - gpu_out_f64(out_dense))
+    say(f"    vs dense fp32 bias path: max abs diff {diff.max():.3e}")
+    assert diff.max() <= 4e-3
+    # the NO_BIAS flag ignores the table; a negative scale and NO_MU go through the same path
+    a = ba.forward_relpos(qb, kb, mq, mk, v, dev(table), x.scale, flags=ba.FLAG_NO_BIAS)
+    b = ba.forward(qb, kb, mq, mk, v, None, x.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    neg = ba.forward_relpos(qb, kb, None, None, v, dev(table), -x.scale, flags=ba.FLAG_NO_MU)
+    torch.cuda.synchronize()
+    ref_neg = gpu_out_f64(ba.forward(qb, kb, None, None, v, dev(dense), -x.scale, flags=ba.FLAG_NO_MU))
+    assert np.abs(gpu_out_f64(neg) - ref_neg).max() <= 4e-3
+
+
+def test_relpos_table_workload_dit_xl2_512_sampled_heads():
+    w = wl.WORKLOADS["dit_xl2_512"]
+    say("relative-position table on dit_xl2_512 (32 x 32 grid)")
+    x = wl.make_inputs(w, device="cuda", with_bias=False)
+    g = torch.Generator().manual_seed(77)
+    table = torch.randn(w.H, 63, 63, generator=g) * 0.02
+    qb, kb, mq, mk = ba.pack_qk(x.q, x.k)
+    out = ba.forward_relpos(qb, kb, mq, mk, x.v, table.cuda(), x.scale)
+    torch.cuda.synchronize()
+    dense = relpos_dense(table, 32, 32)
+    rows = np.unique(np.concatenate([np.arange(0, 24), np.arange(1000, 1024),
+                                     np.random.default_rng(5).integers(0, 1024, 40)]))
+    for (b, h) in [(0, 0), (7, 15), (3, 9)]:
+        q, k, v = (np_bits(t[b, h].cpu()) for t in (x.q, x.k, x.v))
+        vq, delta = orc.quant_v(v)
+        o = orc.attention_rows(q, k, v, dense[h].numpy(), x.scale, orc.abs_mean(q), orc.abs_mean(k), vq,
+                               delta, rows=rows, want=("O2",))
+        check_close(gpu_out_f64(out[b, h])[rows], o["O2"], f"relpos dit_xl2_512 head {(b, h)} vs O2")
+
+
 def test_hip_graph_replay_matches_eager():
     # The library allocates nothing and never synchronises, so a whole step (pack, prepare,
     # attend: five launches at this length, one of them the fill kernel in front of the mu
