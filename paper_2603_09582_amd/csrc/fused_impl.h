@@ -271,9 +271,22 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
             // (as above: the previous item's last block is behind every wave)
             const int LX = 2 * p.Gx - 1, LY = 2 * p.Gy - 1;
             const float *tb = p.table + (int64_t)t.h * LY * LX;
-            for (int i = threadIdx.x; i < LY * TBP; i += FUSED_THREADS * NB) {
+            // (all loads of a thread go out before the first LDS write: one memory latency)
+            constexpr int NTT = FUSED_THREADS * NB;
+            constexpr int TBN = ((2 * TABLE_MAX_G - 1) * TBP + NTT - 1) / NTT;
+            float tv[TBN];
+#pragma unroll
+            for (int j = 0; j < TBN; ++j) {
+                const int i = threadIdx.x + j * NTT;
                 const int ry = i / TBP, kk = i % TBP;
-                tab2[i] = kk < LX ? tb[ry * LX + (LX - 1 - kk)] * inv_alpha : 0.0f;
+                const bool on = i < LY * TBP && kk < LX;
+                tv[j] = tb[on ? ry * LX + (LX - 1 - kk) : 0];
+                if (!on) tv[j] = 0.0f;
+            }
+#pragma unroll
+            for (int j = 0; j < TBN; ++j) {
+                const int i = threadIdx.x + j * NTT;
+                if (i < LY * TBP) tab2[i] = tv[j] * inv_alpha;
             }
             const int qc = min(q, N - 1);
             ax_ub = p.Gx - 1 - (qc & (p.Gx - 1));       // reversed-row index of key column 0
