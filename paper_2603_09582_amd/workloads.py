@@ -74,7 +74,7 @@ for _i, _name in enumerate(SWEEP_HD128):
     _n = int(_name.split("_n")[1])
     WORKLOADS[_name] = Workload(_name, max(1, 16384 // _n), 16, _n, 128, 100 + _i, "",
                                 "head dim 128 sequence-length sweep")
-# Order of the benchmark's `configs` list.
+# The five benchmark configurations, smallest first.
 WORKLOAD_ORDER = ["deit_tiny", "deit_base", "dit_xl2_256", "dit_xl2_512", "vit_hires"]
 
 
