@@ -255,11 +255,36 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
             // barrier), so the tables can be overwritten; a barrier publishes the new ones
             const int LX = 2 * p.Gx - 1, LY = 2 * p.Gy - 1;
             const float *ux = p.ax_x + (int64_t)t.h * LX, *wy = p.ax_y + (int64_t)t.h * LY;
-            for (int i = threadIdx.x; i < 4 * AXL; i += FUSED_THREADS * NB) {
+            // (all loads of a thread go out before the first LDS write: one memory latency)
+            constexpr int NTA = FUSED_THREADS * NB;
+            constexpr int NU = (4 * AXL + NTA - 1) / NTA, NW = (AXL + NTA - 1) / NTA;
+            float tu[NU], tw[NW];
+            int tid = threadIdx.x;  // (opaque: keeps the index arithmetic out of the block loop's registers)
+            asm volatile("" : "+v"(tid));
+#pragma unroll
+            for (int j = 0; j < NU; ++j) {
+                const int i = tid + j * NTA;
                 const int kk = (i % AXL) + (i / AXL);  // index into the reversed table
-                axu[i] = kk < LX ? ux[LX - 1 - kk] * inv_alpha : 0.0f;
+                const bool on = i < 4 * AXL && kk < LX;
+                tu[j] = ux[on ? LX - 1 - kk : 0];
+                if (!on) tu[j] = 0.0f;
             }
-            for (int i = threadIdx.x; i < AXL; i += FUSED_THREADS * NB) axw[i] = i < LY ? wy[i] * inv_alpha : 0.0f;
+#pragma unroll
+            for (int j = 0; j < NW; ++j) {
+                const int i = tid + j * NTA;
+                tw[j] = wy[i < LY ? i : 0];
+                if (i >= LY) tw[j] = 0.0f;
+            }
+#pragma unroll
+            for (int j = 0; j < NU; ++j) {
+                const int i = tid + j * NTA;
+                if (i < 4 * AXL) axu[i] = tu[j] * inv_alpha;
+            }
+#pragma unroll
+            for (int j = 0; j < NW; ++j) {
+                const int i = tid + j * NTA;
+                if (i < AXL) axw[i] = tw[j] * inv_alpha;
+            }
             const int qc = min(q, N - 1);
             const int ix = qc & (p.Gx - 1), iy = qc >> p.gx_shift;
             const int s0 = p.Gx - 1 - ix;  // reversed-table index of key column 0
@@ -274,10 +299,14 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
             // (all loads of a thread go out before the first LDS write: one memory latency)
             constexpr int NTT = FUSED_THREADS * NB;
             constexpr int TBN = ((2 * TABLE_MAX_G - 1) * TBP + NTT - 1) / NTT;
+            // (the thread index is made opaque so that the per-thread table indices are
+            // recomputed here instead of being kept in registers across the whole block loop)
+            int tid = threadIdx.x;
+            asm volatile("" : "+v"(tid));
             float tv[TBN];
 #pragma unroll
             for (int j = 0; j < TBN; ++j) {
-                const int i = threadIdx.x + j * NTT;
+                const int i = tid + j * NTT;
                 const int ry = i / TBP, kk = i % TBP;
                 const bool on = i < LY * TBP && kk < LX;
                 tv[j] = tb[on ? ry * LX + (LX - 1 - kk) : 0];
@@ -285,7 +314,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
             }
 #pragma unroll
             for (int j = 0; j < TBN; ++j) {
-                const int i = threadIdx.x + j * NTT;
+                const int i = tid + j * NTT;
                 if (i < LY * TBP) tab2[i] = tv[j] * inv_alpha;
             }
             const int qc = min(q, N - 1);
