@@ -285,6 +285,25 @@ def main():
                          "attend_ms": r["fused_ms"], "tops_equiv": r["tops_equiv"],
                          "fused_kernel_tops_equiv": r["fused_tops_equiv"],
                          "alu_frac": r["alu_tlaneops"] / ALU_PEAK_TLANEOPS})
+        # ... and the whole layer in one launch where it applies (N <= 256)
+        import torch as _t
+        from paper_2603_09582_amd import binding as _ba
+        w256 = wl.WORKLOADS["dit_xl2_256"]
+        x256 = wl.make_inputs(w256, device="cuda", with_bias=False)
+        gen = _t.Generator(device="cuda").manual_seed(w256.seed + 2000)
+        table = _t.randn(w256.H, 31, 31, generator=gen, device="cuda") * 0.02
+        o256 = _t.empty_like(x256.q)
+        for _ in range(a.warmup):
+            _ba.forward_fused_relpos(x256.q, x256.k, x256.v, table, x256.scale, out=o256)
+        _t.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(max(5, a.steps)):
+            _ba.forward_fused_relpos(x256.q, x256.k, x256.v, table, x256.scale, out=o256)
+        _t.cuda.synchronize()
+        one_ms = (time.perf_counter() - t0) * 1e3 / max(5, a.steps)
+        rows[0]["single_launch_ms_per_step"] = one_ms
+        rows[0]["single_launch_tops_equiv"] = w256.equiv_ops / (one_ms * 1e-3) / 1e12
+        del x256, o256
         line["relpos_table_bias"] = {"note": "b_ij = table[iy-jy][ix-jx], the head's fp32 table held in LDS",
                                      "workloads": rows}
         _, x = run_workload(a.workload, 1, 0)

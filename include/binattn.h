@@ -201,6 +201,17 @@ int binattn_forward_fused(const void *q, const void *k, const void *v, const int
                           float *mu_k_out, unsigned flags, void *stream);
 
 /*
+ * binattn_forward_fused with the relative-position table of binattn_attend_relpos as bias
+ * (table, Gy, Gx as there; Gy * Gx = N <= 256): for a 16 x 16 token grid the whole layer is
+ * one launch and no [N, N] bias exists anywhere.
+ */
+int binattn_forward_fused_relpos(const void *q, const void *k, const void *v, const int64_t q_strides[3],
+                                 const int64_t k_strides[3], const int64_t v_strides[3], const float *table,
+                                 int Gy, int Gx, float scale, int B, int H, int N, int d, void *out,
+                                 const int64_t out_strides[3], float *mu_q_out, float *mu_k_out,
+                                 unsigned flags, void *stream);
+
+/*
  * Integer logits I_ij = s_i . t_j of Sec. 4.1 for query rows
  * [row_begin, row_end) of every head: int32 [B, H, row_end - row_begin, N]
  * contiguous.  BINATTN_LOGITS_MFMA_FP4 runs the same tile routine as the fused

@@ -22,6 +22,7 @@ LOGITS_POPCOUNT, LOGITS_MFMA_I8, LOGITS_MFMA_FP4 = 0, 1, 2
 EXPORTS = ["binattn_version", "binattn_strerror", "binattn_pack_qk", "binattn_workspace_bytes",
            "binattn_prepare_kv", "binattn_attend", "binattn_forward", "binattn_attend_axial",
            "binattn_forward_axial", "binattn_attend_relpos", "binattn_forward_relpos", "binattn_forward_fused",
+           "binattn_forward_fused_relpos",
            "binattn_logits_debug", "binattn_quant_v_debug"]
 
 _lib = None
@@ -80,6 +81,9 @@ def lib():
     L.binattn_forward_fused.restype = C.c_int
     L.binattn_forward_fused.argtypes = [vp, vp, vp, i64p, i64p, i64p, vp, C.c_int, i64p, C.c_float, C.c_int,
                                         C.c_int, C.c_int, C.c_int, vp, i64p, vp, vp, C.c_uint, vp]
+    L.binattn_forward_fused_relpos.restype = C.c_int
+    L.binattn_forward_fused_relpos.argtypes = [vp, vp, vp, i64p, i64p, i64p, vp, C.c_int, C.c_int, C.c_float,
+                                               C.c_int, C.c_int, C.c_int, C.c_int, vp, i64p, vp, vp, C.c_uint, vp]
     L.binattn_logits_debug.restype = C.c_int
     L.binattn_logits_debug.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                        vp, C.c_int, vp, C.c_size_t, vp]
@@ -296,6 +300,24 @@ def forward_fused(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bias: Optio
         None if mu_q is None else mu_q.data_ptr(), None if mu_k is None else mu_k.data_ptr(),
         int(flags), _stream())
     _check(rc, "binattn_forward_fused")
+    return out
+
+
+def forward_fused_relpos(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, table: torch.Tensor, scale: float,
+                         out: Optional[torch.Tensor] = None, mu_q: Optional[torch.Tensor] = None,
+                         mu_k: Optional[torch.Tensor] = None, flags: int = 0) -> torch.Tensor:
+    """binattn_forward_fused_relpos: one launch, bias from the head's relative-position table (N <= 256)."""
+    assert q.dtype == k.dtype == v.dtype == torch.bfloat16 and q.is_cuda
+    B, H, N, d = q.shape
+    Gy, Gx = _relpos_table(table, H)
+    if out is None:
+        out = torch.empty(B, H, N, d, dtype=torch.bfloat16, device=q.device)
+    rc = lib().binattn_forward_fused_relpos(
+        q.data_ptr(), k.data_ptr(), v.data_ptr(), _strides3(q), _strides3(k), _strides3(v), table.data_ptr(),
+        Gy, Gx, float(scale), B, H, N, d, out.data_ptr(), _strides3(out),
+        None if mu_q is None else mu_q.data_ptr(), None if mu_k is None else mu_k.data_ptr(),
+        int(flags), _stream())
+    _check(rc, "binattn_forward_fused_relpos")
     return out
 
 

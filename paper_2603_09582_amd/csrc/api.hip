@@ -37,7 +37,7 @@ int check_workspace(const void *ws, size_t bytes, const Workspace &w) {
 
 extern "C" {
 
-int binattn_version(void) { return 130; }
+int binattn_version(void) { return 131; }
 
 const char *binattn_strerror(int code) {
     switch (code) {
@@ -356,25 +356,55 @@ int binattn_forward_relpos(const uint32_t *q_bits, const uint32_t *k_bits, const
                                  workspace, workspace_bytes, flags, stream);
 }
 
+}  // extern "C" (reopened below)
+
+namespace {
+// arguments of the single-launch forms: bf16 inputs and optional abs-mean exports
+int check_raw(const void *q, const void *k, const void *v, const int64_t q_strides[3],
+              const int64_t k_strides[3], const int64_t v_strides[3], int B, int H, int N, int d,
+              const void *out, float *mu_q_out, float *mu_k_out, RawInputs *raw) {
+    if (!q || !k || !v || !out) return BINATTN_ERR_NULL;
+    if (!shape_ok(B, H, N, d) || N > 2 * BV) return BINATTN_ERR_SHAPE;
+    const Shape s = make_shape(B, H, N, d);
+    int rc;
+    if ((rc = check_strides_bhnd(q_strides, s, &raw->qs)) != BINATTN_OK) return rc;
+    if ((rc = check_strides_bhnd(k_strides, s, &raw->ks)) != BINATTN_OK) return rc;
+    if ((rc = check_strides_bhnd(v_strides, s, &raw->vs)) != BINATTN_OK) return rc;
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16)) return BINATTN_ERR_ALIGN;
+    if ((mu_q_out && !aligned(mu_q_out, 4)) || (mu_k_out && !aligned(mu_k_out, 4))) return BINATTN_ERR_ALIGN;
+    raw->q = q; raw->k = k; raw->v = v;
+    raw->mu_q_out = mu_q_out; raw->mu_k_out = mu_k_out;
+    return BINATTN_OK;
+}
+}  // namespace
+
+extern "C" {
+
 int binattn_forward_fused(const void *q, const void *k, const void *v, const int64_t q_strides[3],
                           const int64_t k_strides[3], const int64_t v_strides[3], const void *bias,
                           int bias_dtype, const int64_t bias_strides[3], float scale, int B, int H, int N,
                           int d, void *out, const int64_t out_strides[3], float *mu_q_out,
                           float *mu_k_out, unsigned flags, void *stream) {
-    if (!q || !k || !v || !out) return BINATTN_ERR_NULL;
-    if (!shape_ok(B, H, N, d) || N > 2 * BV) return BINATTN_ERR_SHAPE;
-    const Shape s = make_shape(B, H, N, d);
     RawInputs raw;
-    int rc;
-    if ((rc = check_strides_bhnd(q_strides, s, &raw.qs)) != BINATTN_OK) return rc;
-    if ((rc = check_strides_bhnd(k_strides, s, &raw.ks)) != BINATTN_OK) return rc;
-    if ((rc = check_strides_bhnd(v_strides, s, &raw.vs)) != BINATTN_OK) return rc;
-    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16)) return BINATTN_ERR_ALIGN;
-    if ((mu_q_out && !aligned(mu_q_out, 4)) || (mu_k_out && !aligned(mu_k_out, 4))) return BINATTN_ERR_ALIGN;
-    raw.q = q; raw.k = k; raw.v = v;
-    raw.mu_q_out = mu_q_out; raw.mu_k_out = mu_k_out;
+    const int rc = check_raw(q, k, v, q_strides, k_strides, v_strides, B, H, N, d, out, mu_q_out, mu_k_out, &raw);
+    if (rc != BINATTN_OK) return rc;
     return attend_impl(nullptr, nullptr, nullptr, bias, bias_dtype, bias_strides, nullptr, &raw, scale, B, H,
                        N, d, out, out_strides, nullptr, 0, flags, stream);
+}
+
+int binattn_forward_fused_relpos(const void *q, const void *k, const void *v, const int64_t q_strides[3],
+                                 const int64_t k_strides[3], const int64_t v_strides[3], const float *table,
+                                 int Gy, int Gx, float scale, int B, int H, int N, int d, void *out,
+                                 const int64_t out_strides[3], float *mu_q_out, float *mu_k_out,
+                                 unsigned flags, void *stream) {
+    if (!table) return BINATTN_ERR_NULL;
+    RawInputs raw;
+    const int rc = check_raw(q, k, v, q_strides, k_strides, v_strides, B, H, N, d, out, mu_q_out, mu_k_out, &raw);
+    if (rc != BINATTN_OK) return rc;
+    AxialBias ax = {nullptr, nullptr, Gy, Gx};
+    ax.table = table;
+    return attend_impl(nullptr, nullptr, nullptr, nullptr, 0, nullptr, &ax, &raw, scale, B, H, N, d, out,
+                       out_strides, nullptr, 0, flags, stream);
 }
 
 int binattn_logits_debug(const uint32_t *q_bits, const uint32_t *k_bits, int B, int H, int N, int d,

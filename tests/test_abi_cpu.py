@@ -153,6 +153,20 @@ def test_forward_fused_rejects_bad_arguments():
     assert fused(bs=st(0, 100, 8)) == -3
 
 
+def fused_relpos(q=FAKE, v=FAKE, out=FAKE, table=FAKE, Gy=16, Gx=16, N=256, d=64, mq=FAKE):
+    B, H = 2, 2
+    s3 = st(H * N * d, N * d, d)
+    return ba.lib().binattn_forward_fused_relpos(q, FAKE, v, s3, s3, s3, table, Gy, Gx, 0.125, B, H, N, d, out, s3,
+                                                 mq, None, 0, None)
+
+
+def test_forward_fused_relpos_rejects_bad_arguments():
+    assert fused_relpos(table=None) == -1 and fused_relpos(q=None) == -1 and fused_relpos(out=None) == -1
+    assert fused_relpos(Gy=32, Gx=16, N=512) == -2          # more than two key blocks
+    assert fused_relpos(Gy=15) == -2 and fused_relpos(Gx=8, Gy=32) == -2
+    assert fused_relpos(table=FAKE + 2) == -4 and fused_relpos(v=FAKE + 8) == -4 and fused_relpos(mq=FAKE + 1) == -4
+
+
 def test_debug_entry_points_reject_bad_arguments():
     L = ba.lib()
     f = lambda **k: L.binattn_logits_debug(

@@ -492,6 +492,29 @@ def test_relpos_table_matches_dense_oracle(B, H, Gy, Gx, d):
     assert np.abs(gpu_out_f64(neg) - ref_neg).max() <= 4e-3
 
 
+@pytest.mark.parametrize("B,H,Gy,Gx,d", [(2, 3, 16, 16, 72), (1, 2, 8, 16, 64), (1, 1, 4, 32, 128), (3, 1, 1, 16, 32)])
+def test_forward_fused_relpos_matches_oracle(B, H, Gy, Gx, d):
+    N = Gy * Gx
+    say(f"single-launch forward with relative-position table B={B} H={H} grid {Gy}x{Gx} d={d}")
+    x = small_inputs(B, H, N, d, 650 + Gy)
+    g = torch.Generator().manual_seed(Gy * 10 + Gx)
+    table = torch.randn(H, 2 * Gy - 1, 2 * Gx - 1, generator=g) * 0.7
+    dense = relpos_dense(table, Gy, Gx)
+    mq = torch.zeros(B, H, dtype=torch.float32, device="cuda")
+    mk = torch.zeros_like(mq)
+    out = ba.forward_fused_relpos(dev(x.q), dev(x.k), dev(x.v), dev(table), x.scale, mu_q=mq, mu_k=mk)
+    torch.cuda.synchronize()
+    got = gpu_out_f64(out)
+    check_close(got, oracle_forward(x, dense)["O2"], "single-launch relpos: out vs O2 (dense oracle)")
+    for b in range(B):
+        for h in range(H):
+            assert float(mq[b, h]) == pytest.approx(orc.abs_mean(np_bits(x.q[b, h])), rel=2e-6)
+    # and against the three-call path with the same table
+    qb, kb, mq3, mk3 = ba.pack_qk(dev(x.q), dev(x.k))
+    three = gpu_out_f64(ba.forward_relpos(qb, kb, mq3, mk3, dev(x.v), dev(table), x.scale))
+    assert np.abs(got - three).max() <= 2e-3
+
+
 def test_relpos_table_workload_dit_xl2_512_sampled_heads():
     w = wl.WORKLOADS["dit_xl2_512"]
     say("relative-position table on dit_xl2_512 (32 x 32 grid)")
