@@ -639,7 +639,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         // phi and psi of Alg. 1 for this head, straight into the two LDS images.
         constexpr int NT = FUSED_THREADS * NB;
         __shared__ int sabs[DKP];            // per-channel absmax of V (bit patterns)
-        __shared__ __attribute__((aligned(16))) float srcp[DKP], sthr[DKP];  // bracketing reciprocals of delta_v
+        __shared__ __attribute__((aligned(16))) float srlo[DKP], srhi[DKP];  // bracketing reciprocals of delta_v
         __shared__ float ssum[2][NT / 64];   // |q| and |k| partial sums per wave
         const int C16 = d / 8, nblk = p.nblk;
         auto imgp = [&](int blk) -> char * { return blk ? bufB : bufA; };
@@ -759,7 +759,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         __syncthreads();
         if (threadIdx.x < 8 * C16) {
             float dl;
-            quant_consts(__int_as_float(sabs[threadIdx.x]), &dl, &srcp[threadIdx.x], &sthr[threadIdx.x]);
+            quant_consts(__int_as_float(sabs[threadIdx.x]), &dl, &srlo[threadIdx.x], &srhi[threadIdx.x]);
             sdelta[0][0][threadIdx.x] = dl;
         }
         float tq = 0.0f, tk = 0.0f;
@@ -778,7 +778,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         __syncthreads();
         // V codes, channel-major, into the images
         if (von) {
-            const QuantConsts8 kc = load_quant_consts8(&sdelta[0][0][0], srcp, sthr, vc);
+            const QuantConsts8 kc = load_quant_consts8(&sdelta[0][0][0], srlo, srhi, vc);
 #pragma unroll
             for (int kq = 0; kq < 2; ++kq) {
                 const int quad = vr + kq * RT;

@@ -90,7 +90,7 @@ __device__ __forceinline__ float absmax_rows(const uint16_t *__restrict__ vb, in
 template <int C16>
 __device__ __forceinline__ void quant_v_block(const uint16_t *__restrict__ vb, int64_t stride_n,
                                               int N, int DKP, int blk, const float *sdelta,
-                                              const float *srcp, const float *sthr, int8_t *tile,
+                                              const float *srlo, const float *srhi, int8_t *tile,
                                               int v_off, int cs_off, char *__restrict__ dst) {
     constexpr int LDT = BV + 16;  // LDS row pitch in bytes = Image::VP
     for (int i = threadIdx.x; i < DKP * LDT / 4; i += PREP_THREADS)
@@ -114,7 +114,7 @@ __device__ __forceinline__ void quant_v_block(const uint16_t *__restrict__ vb, i
             if (4 * jq + k < nrow)
                 w[k] = *reinterpret_cast<const u4 *>(vb + (int64_t)(j0 + 4 * jq + k) * stride_n + 8 * c);
         }
-        quant_quad(w, load_quant_consts8(sdelta, srcp, sthr, c), packed);
+        quant_quad(w, load_quant_consts8(sdelta, srlo, srhi, c), packed);
         const int col = jq ^ (((c >> 1) & 3) << 3);
 #pragma unroll
         for (int i = 0; i < 8; ++i)
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(
     const uint16_t *__restrict__ v, Strides3 vs, const uint32_t *__restrict__ k_bits, int H, int N,
     int d, int DKP, int nchunk, int nblk, const float *__restrict__ amax, float *__restrict__ delta,
     int img_bytes, int KP, int v_off, int cs_off, char *__restrict__ img) {
-    __shared__ __attribute__((aligned(16))) float sdelta[8 * C16], srcp[8 * C16], sthr[8 * C16];
+    __shared__ __attribute__((aligned(16))) float sdelta[8 * C16], srlo[8 * C16], srhi[8 * C16];
     __shared__ __attribute__((aligned(16))) int8_t tile[128 * (BV + 16)];
     const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
     const int b = bh / H, h = bh % H;
@@ -197,11 +197,11 @@ __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(
     __syncthreads();
     if (threadIdx.x < 8 * C16) {
         float dl;
-        quant_consts(__int_as_float(sabs[threadIdx.x]), &dl, &srcp[threadIdx.x], &sthr[threadIdx.x]);
+        quant_consts(__int_as_float(sabs[threadIdx.x]), &dl, &srlo[threadIdx.x], &srhi[threadIdx.x]);
         sdelta[threadIdx.x] = dl;
         if (blk == 0) delta[(int64_t)bh * DKP + threadIdx.x] = dl;
     }
-    quant_v_block<C16>(vb, vs.n, N, DKP, blk, sdelta, srcp, sthr, tile, v_off, cs_off, dst);
+    quant_v_block<C16>(vb, vs.n, N, DKP, blk, sdelta, srlo, srhi, tile, v_off, cs_off, dst);
 }
 
 // Short sequences (at most two key blocks): everything for one head in ONE launch and ONE
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(PREP_THREADS) void prep_head_kernel(
     constexpr int MAXQ = (NQ + RT - 1) / RT;
     constexpr int LDT = BV + 16;            // = Image::VP
     __shared__ float smax[RT * D];
-    __shared__ __attribute__((aligned(16))) float sdelta[D], srcp[D], sthr[D];
+    __shared__ __attribute__((aligned(16))) float sdelta[D], srlo[D], srhi[D];
     __shared__ __attribute__((aligned(16))) int8_t tile[2 * 128 * LDT];
     const int bh = blockIdx.x, b = bh / H, h = bh % H;
     const int W = (d + 31) / 32;
@@ -259,14 +259,14 @@ __global__ __launch_bounds__(PREP_THREADS) void prep_head_kernel(
         float a = 0.0f;
         for (int r = 0; r < RT; ++r) a = fmaxf(a, smax[r * D + threadIdx.x]);
         float dl;
-        quant_consts(a, &dl, &srcp[threadIdx.x], &sthr[threadIdx.x]);
+        quant_consts(a, &dl, &srlo[threadIdx.x], &srhi[threadIdx.x]);
         sdelta[threadIdx.x] = dl;
         delta[(int64_t)bh * DKP + threadIdx.x] = dl;
     }
     __syncthreads();
 
     if (on) {
-        const QuantConsts8 kc = load_quant_consts8(sdelta, srcp, sthr, c);
+        const QuantConsts8 kc = load_quant_consts8(sdelta, srlo, srhi, c);
 #pragma unroll
         for (int k = 0; k < MAXQ; ++k) {
             const int quad = r0 + k * RT;
