@@ -26,7 +26,7 @@
 //   5. O = exp(m_old - m_new) * O + block result (Alg. 1's rescale line, read as
 //      a multiplication) is one FMA per output register; the 1.5 * 2^23 offsets
 //      accumulate as 1.5 * 2^23 * rho with rho = sum of the rescale products,
-//      tracked per row and subtracted once at the end.
+//      tracked per row and subtracted every eighth block and at the end.
 // Final: (O - 1.5*2^23*rho) / (sum of 255 * P_hat) * delta_v (Alg. 1 last line;
 // the factor 255 is already inside the row sum).
 #pragma once
@@ -101,6 +101,8 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     // exponential phase (the rest just before their MFMAs): hides the LDS latency
     // where the register budget allows it.
     constexpr int PRE = DK <= 2 ? DK : 1;
+    // key blocks between two removals of the accumulator's float-bit offset (a power of two)
+    constexpr int REBASE = 8;
     __shared__ __attribute__((aligned(1024))) char bufA[NIMG * L::BYTES];
     __shared__ __attribute__((aligned(1024))) char bufB[NIMG * L::BYTES];
     // BIAS_BF16_LDS: staging of the 32 x 128 bias tiles, 8 KiB per 32-row group.
@@ -613,6 +615,16 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         for (int cb = 0; cb < DK; ++cb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) Of[cb][r] = fmaf(Of[cb][r], resc, __int_as_float(acc[cb][r]));
+        //    The carried offset 1.5 * 2^23 * rho sets the carry's rounding unit: it is taken out
+        //    every REBASE blocks (one FMA per output register), so that rho <= REBASE and a block
+        //    result is rounded to at most 8 units of the integer accumulator whatever N is.
+        if ((it & (REBASE - 1)) == REBASE - 1) {
+#pragma unroll
+            for (int cb = 0; cb < DK; ++cb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) Of[cb][r] = fmaf(-PV_MAGIC_F, rho, Of[cb][r]);
+            rho = 0.0f;
+        }
 
         __builtin_amdgcn_sched_barrier(0);  // keep the wait at the very end of the block
         wait_vmem();      // this wave's copies for the next block have landed

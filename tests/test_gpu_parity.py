@@ -679,7 +679,63 @@ def test_forward_fused_more_heads_than_cus(layout):
     assert np.abs(got - run_forward(x, x.bias)).max() <= 2e-3
 
 
-# ---- the five workloads ----------------------------------------------------------
+# ---- the five workloads, at full size, in the launch configuration bench.py times --------
+def _workload_check(name, heads=None, rows=None, rows_per_head=None, with_bias=True):
+    """Run pack_qk + forward on workload `name` and compare with the oracle, head by head.
+    heads: list of (b, h), None = every head.  rows: query rows checked on every head (None =
+    all rows); rows_per_head(b, h) -> extra rows for that head.  Sign words, mu and outputs
+    are compared for every head listed."""
+    w = wl.WORKLOADS[name]
+    N = w.N
+    x = wl.make_inputs(w, device="cuda", with_bias=with_bias)
+    qb, kb, mq, mk = ba.pack_qk(x.q, x.k)
+    out = ba.forward(qb, kb, mq, mk, x.v, x.bias, x.scale)
+    torch.cuda.synchronize()
+    if heads is None:
+        heads = [(b, h) for h in range(w.H) for b in range(w.B)]
+    heads = sorted(heads, key=lambda t: (t[1], t[0]))       # head-major: one bias slab at a time
+    say(f"workload {name}: {len(heads)} of {w.B * w.H} heads, "
+        f"{'all' if rows is None and rows_per_head is None else 'sampled'} rows")
+    qh, kh, vh = (np_bits(t) for t in (x.q, x.k, x.v))
+    qbh, kbh = (t.cpu().numpy().view(np.uint32) for t in (qb, kb))
+    mqh, mkh = mq.cpu().numpy(), mk.cpu().numpy()
+    base_rows = np.arange(N) if rows is None else np.unique(np.asarray(rows, dtype=np.int64))
+    outh = np_bits(out) if rows is None else None
+    small_bias = with_bias and rows is None and rows_per_head is None
+    full = None if (small_bias or not with_bias) else np.zeros((N, N), dtype=np.uint16)
+    bias_h, bias_of = None, -1
+    worst, nrows = 0.0, 0
+    for (b, h) in heads:
+        q, k, v = qh[b, h], kh[b, h], vh[b, h]
+        assert np.array_equal(qbh[b, h], orc.sign_pack(q)), f"{name} head {(b, h)}: q sign words"
+        assert np.array_equal(kbh[b, h], orc.sign_pack(k)), f"{name} head {(b, h)}: k sign words"
+        mu_q, mu_k = orc.abs_mean(q), orc.abs_mean(k)
+        assert float(mqh[b, h]) == pytest.approx(mu_q, rel=5e-6), f"{name} head {(b, h)}: mu_q"
+        assert float(mkh[b, h]) == pytest.approx(mu_k, rel=5e-6), f"{name} head {(b, h)}: mu_k"
+        vq, delta = orc.quant_v(v)
+        r = base_rows
+        if rows_per_head is not None:
+            r = np.unique(np.concatenate([base_rows, np.asarray(rows_per_head(b, h), dtype=np.int64)]))
+        rt = torch.as_tensor(r, device="cuda")
+        if not with_bias:
+            bias = None
+        elif small_bias:
+            if bias_of != h:
+                bias_h, bias_of = np_bits(x.bias[h]), h
+            bias = bias_h
+        else:                      # only the sampled rows of the [N, N] slab travel to the host
+            full[r] = np_bits(x.bias[h][rt])
+            bias = full
+        o = orc.attention_rows(q, k, v, bias, x.scale, mu_q, mu_k, vq, delta, rows=r, want=("O2",))["O2"]
+        got = bits_to_f64(outh[b, h]) if outh is not None else gpu_out_f64(out[b, h][rt])
+        err = np.abs(got - o)
+        over = float((err - (ATOL + RTOL * np.abs(o))).max())
+        assert over <= 0, f"{name} head {(b, h)}: tolerance exceeded by {over:.3e} (max abs err {err.max():.3e})"
+        worst = max(worst, float(err.max()))
+        nrows += len(r)
+    say(f"    {name}: {nrows} rows x {w.d} channels checked, max abs err {worst:.3e}")
+
+
 def test_workload_deit_tiny_full():
     w = wl.WORKLOADS["deit_tiny"]
     say(f"workload {w.name}")
@@ -690,63 +746,107 @@ def test_workload_deit_tiny_full():
     say(f"    method's own quantisation error |O2-O1| max {np.abs(ref['O2'] - ref['O1']).max():.3e}")
 
 
-def _sampled_check(name, heads, rows, seed_device="cuda"):
-    w = wl.WORKLOADS[name]
-    say(f"workload {w.name} (sampled heads {heads}, {len(rows)} rows)")
-    x = wl.make_inputs(w, device=seed_device)
-    qb, kb, mq, mk = ba.pack_qk(x.q, x.k)
-    out = ba.forward(qb, kb, mq, mk, x.v, x.bias, x.scale)
-    torch.cuda.synchronize()
-    rows_np = np.asarray(rows, dtype=np.int64)
-    for (b, h) in heads:
-        q, k, v = (np_bits(t[b, h].cpu()) for t in (x.q, x.k, x.v))
-        # integer checkpoints
-        assert np.array_equal(qb[b, h].cpu().numpy().view(np.uint32), orc.sign_pack(q))
-        assert np.array_equal(kb[b, h].cpu().numpy().view(np.uint32), orc.sign_pack(k))
-        mu_q, mu_k = orc.abs_mean(q), orc.abs_mean(k)
-        assert float(mq[b, h]) == pytest.approx(mu_q, rel=5e-6)
-        vq, delta = orc.quant_v(v)
-        brows = np_bits(x.bias[h][torch.as_tensor(rows_np, device=x.bias.device)].cpu())
-        # the oracle takes an [N, N] bias; hand it only the sampled rows via a row-compacted copy
-        full = np.zeros((w.N, w.N), dtype=np.uint16)
-        full[rows_np] = brows
-        o = orc.attention_rows(q, k, v, full, x.scale, mu_q, mu_k, vq, delta, rows=rows_np, want=("O2",))
-        got = gpu_out_f64(out[b, h][torch.as_tensor(rows_np, device=out.device)])
-        check_close(got, o["O2"], f"{name} head {(b, h)} vs O2")
+def test_workload_deit_base_every_head_every_row():
+    _workload_check("deit_base")
 
 
-def test_workload_deit_base_sampled_heads():
-    N = wl.WORKLOADS["deit_base"].N
-    _sampled_check("deit_base", [(0, 0), (17, 5), (63, 11)], list(range(N)))
+def test_workload_dit_xl2_256_every_head_every_row():
+    _workload_check("dit_xl2_256")
 
 
-def test_workload_dit_xl2_256_sampled_heads():
-    N = wl.WORKLOADS["dit_xl2_256"].N
-    _sampled_check("dit_xl2_256", [(0, 0), (31, 15), (13, 7)], list(range(N)))
+def test_workload_dit_xl2_512_every_head_every_row():
+    _workload_check("dit_xl2_512")
 
 
-def test_workload_dit_xl2_512_sampled_heads():
-    N = wl.WORKLOADS["dit_xl2_512"].N
-    rows = list(range(0, 64)) + list(range(480, 544)) + list(range(N - 64, N))
-    _sampled_check("dit_xl2_512", [(0, 0), (7, 15), (3, 9)], rows)
-
-
-def test_workload_vit_hires_sampled_rows():
+def test_workload_vit_hires_every_head_sampled_rows():
+    # first, middle and last row blocks of every head plus 256 seeded rows per head, every key
     N = wl.WORKLOADS["vit_hires"].N
-    rng = np.random.default_rng(0)
-    rows = sorted(set(list(range(0, 32)) + list(range(8160, 8192)) + list(range(N - 32, N)) +
-                      rng.integers(0, N, 64).tolist()))
-    _sampled_check("vit_hires", [(0, 0), (1, 15)], rows)
+    fixed = list(range(0, 64)) + list(range(8160, 8224)) + list(range(N - 64, N))
+    _workload_check("vit_hires", rows=fixed,
+                    rows_per_head=lambda b, h: np.random.default_rng(1000 + 16 * b + h).integers(0, N, 256))
 
 
-def test_sweep_hd128_sampled_rows():
-    # head dimension 128 (four channel blocks, register-path bias): the kernel-speed setting
-    name = "hd128_n4096"
-    N = wl.WORKLOADS[name].N
-    rng = np.random.default_rng(1)
-    rows = sorted(set(list(range(0, 16)) + list(range(N - 16, N)) + rng.integers(0, N, 32).tolist()))
-    _sampled_check(name, [(0, 0), (3, 15)], rows)
+@pytest.mark.parametrize("name,with_bias", [("hd128_n4096", True), ("hd128_n16384", True), ("hd128_n32768", False)])
+def test_sweep_hd128_sampled_rows(name, with_bias):
+    # head dimension 128 (four channel blocks), the kernel-speed setting: with a dense bias
+    # (8-wave row-pair workgroups, LDS bias tiles) and, at the longest length, without
+    w = wl.WORKLOADS[name]
+    N = w.N
+    fixed = list(range(0, 16)) + list(range(N // 2 - 8, N // 2 + 8)) + list(range(N - 16, N))
+    heads = [(0, 0), (w.B - 1, 15), (0, 7), (w.B - 1, 4)]
+    _workload_check(name, heads=sorted(set(heads)), rows=fixed, with_bias=with_bias,
+                    rows_per_head=lambda b, h: np.random.default_rng(50 + h).integers(0, N, 48))
 
+
+def test_axial_bias_at_the_128x128_grid_sampled_rows():
+    # the decomposed relative-position bias at the long-sequence workload's own grid
+    w = wl.WORKLOADS["vit_hires"]
+    N, Gy, Gx = w.N, 128, 128
+    say("axial bias on vit_hires (128 x 128 grid)")
+    x = wl.make_inputs(w, device="cuda", with_bias=False)
+    g = torch.Generator().manual_seed(4128)
+    by = torch.randn(w.H, 2 * Gy - 1, generator=g) * 0.3
+    bx = torch.randn(w.H, 2 * Gx - 1, generator=g) * 0.3
+    qb, kb, mq, mk = ba.pack_qk(x.q, x.k)
+    out = ba.forward_axial(qb, kb, mq, mk, x.v, by.cuda(), bx.cuda(), x.scale)
+    torch.cuda.synchronize()
+    qh, kh, vh = (np_bits(t) for t in (x.q, x.k, x.v))
+    fixed = np.concatenate([np.arange(0, 40), np.arange(8170, 8210), np.arange(N - 40, N)])
+    n = np.arange(N)
+    jy, jx = n // Gx, n % Gx
+    full = np.zeros((N, N), dtype=np.float32)
+    worst = 0.0
+    for h in range(w.H):
+        for b in range(w.B):
+            r = np.unique(np.concatenate([fixed, np.random.default_rng(7 * h + b).integers(0, N, 40)]))
+            iy, ix = r // Gx, r % Gx
+            full[r] = (by[h].numpy()[iy[:, None] - jy[None, :] + Gy - 1] +
+                       bx[h].numpy()[ix[:, None] - jx[None, :] + Gx - 1])
+            q, k, v = qh[b, h], kh[b, h], vh[b, h]
+            vq, delta = orc.quant_v(v)
+            o = orc.attention_rows(q, k, v, full, x.scale, orc.abs_mean(q), orc.abs_mean(k), vq, delta,
+                                   rows=r, want=("O2",))["O2"]
+            got = gpu_out_f64(out[b, h][torch.as_tensor(r, device="cuda")])
+            err = np.abs(got - o)
+            assert np.all(err <= ATOL + RTOL * np.abs(o)), f"axial 128x128 head {(b, h)}: max abs err {err.max():.3e}"
+            worst = max(worst, float(err.max()))
+    say(f"    axial 128x128: max abs err {worst:.3e}")
+
+
+@pytest.mark.parametrize("B,H,N,d,kind", [(2, 1, 16384, 64, "one_hot"), (2, 1, 16384, 64, "few_visible"),
+                                          (1, 1, 32768, 128, "one_hot"), (1, 1, 16384, 72, "few_visible")])
+def test_peaked_rows_at_long_sequences(B, H, N, d, kind):
+    # Rows whose whole weight sits on a few EARLY keys: every later block adds (almost) nothing
+    # to a carry that must survive more than a hundred rescale steps unharmed.  Compared with
+    # Alg. 1 at the kernel's block size, where only fp32-vs-fp64 rounding remains.
+    say(f"peaked rows B={B} H={H} N={N} d={d} {kind}")
+    x = wl.make_inputs(wl.custom_workload(B, H, N, d, 8000 + d), device="cuda", with_bias=False)
+    bias = torch.zeros(H, N, N, dtype=torch.bfloat16, device="cuda")
+    rows = np.unique(np.concatenate([np.arange(0, 8), np.arange(N - 8, N),
+                                     np.random.default_rng(d).integers(0, N, 48)]))
+    if kind == "one_hot":        # +50 on one key among the first hundred
+        star = (torch.arange(N, device="cuda") * 7 + 3) % 100
+        bias[:, torch.arange(N, device="cuda"), star] = 50.0
+    else:                        # everything masked but five early keys
+        bias.fill_(float("-inf"))
+        bias[:, :, 3:8] = torch.tensor([0.5, -1.0, 2.0, 0.0, 1.0], dtype=torch.bfloat16, device="cuda")
+    qb, kb, mq, mk = ba.pack_qk(x.q, x.k)
+    out = ba.forward(qb, kb, mq, mk, x.v, bias, x.scale)
+    torch.cuda.synchronize()
+    rt = torch.as_tensor(rows, device="cuda")
+    full = np.zeros((N, N), dtype=np.uint16)
+    for b in range(B):
+        for h in range(H):
+            q, k, v = (np_bits(t[b, h]) for t in (x.q, x.k, x.v))
+            vq, delta = orc.quant_v(v)
+            full[rows] = np_bits(bias[h][rt])
+            ref = orc.algorithm1_rows(q, k, v, full, x.scale, orc.abs_mean(q), orc.abs_mean(k), vq, delta,
+                                      Bv=128, quantise=True, rows=rows)
+            got = gpu_out_f64(out[b, h][rt])
+            assert np.isfinite(got).all()
+            err = np.abs(got - ref)
+            say(f"    head {(b, h)} vs Alg.1(Bv=128): max abs err {err.max():.3e} (max delta_v {float(delta.max()):.3e})")
+            assert np.all(err <= 2e-3 + 2 ** -7 * np.abs(ref))
 
 
 def test_against_stored_oracle_outputs():
