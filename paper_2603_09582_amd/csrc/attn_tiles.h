@@ -32,17 +32,6 @@ typedef unsigned u4v __attribute__((ext_vector_type(4)));  // 16-byte register
 constexpr int FUSED_THREADS = 256;
 constexpr int KT = BV / 32;  // MFMA key tiles per block
 
-// FP4 e2m1 codes
-constexpr unsigned FP4_PLUS1 = 0x2u, FP4_MINUS1 = 0xAu;
-
-// 8 sign bits -> 8 FP4 nibbles (bit i -> nibble i): +1.0 where set, -1.0 where clear.
-__device__ __forceinline__ unsigned fp4_pm1_from_bits8(unsigned b) {
-    unsigned x = (b | (b << 12)) & 0x000F000Fu;  // 4 bits per half word
-    x = (x | (x << 6)) & 0x03030303u;            // 2 bits per byte
-    x = (x | (x << 3)) & 0x11111111u;            // 1 bit per nibble, at its lowest position
-    return 0xAAAAAAAAu - (x << 3);               // 0xA - 8 = 0x2 where the bit is set
-}
-
 // B operand of the QK tile for this lane's query row: FP4 codes of channels
 // 64 s + 32 g + [0, 32) in 16 bytes, zero beyond d.  q_words: the row's sign words
 // (zero-filled up to 2 * DK2).  `flip` negates the row, `zero` clears it (used for a

@@ -68,6 +68,17 @@ __host__ __device__ inline int k_chunk(int pos, int chunk, int KP) {
     return KP == 32 ? (chunk ^ ((pos >> 3) & 1)) : (chunk ^ ((pos >> 2) & 3));
 }
 
+// FP4 e2m1 codes of +1.0 and -1.0
+constexpr unsigned FP4_PLUS1 = 0x2u, FP4_MINUS1 = 0xAu;
+
+// 8 sign bits -> 8 FP4 nibbles (bit i -> nibble i): +1.0 where set, -1.0 where clear.
+__device__ __forceinline__ unsigned fp4_pm1_from_bits8(unsigned b) {
+    unsigned x = (b | (b << 12)) & 0x000F000Fu;  // 4 bits per half word
+    x = (x | (x << 6)) & 0x03030303u;            // 2 bits per byte
+    x = (x | (x << 3)) & 0x11111111u;            // 1 bit per nibble, at its lowest position
+    return 0xAAAAAAAAu - (x << 3);               // 0xA - 8 = 0x2 where the bit is set
+}
+
 inline int image_bytes(int DK) {
     switch (DK) {
         case 1: return Image<1>::BYTES;

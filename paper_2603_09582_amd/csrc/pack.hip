@@ -4,7 +4,7 @@
 // channels of one token), turns them into 8 sign bits and one partial |x| sum.
 // The sign bytes of a tile of tokens are assembled in LDS and written out as
 // whole uint32 words, fully coalesced.  Q and K go through one launch.
-#include "binattn_internal.h"
+#include "quant_v.h"
 
 namespace binattn {
 
@@ -19,22 +19,7 @@ __global__ void zero_f32_kernel(float *a, float *b, int n) {
     }
 }
 
-// bit = (x >= 0) under IEEE rules, so -0.0 -> 1 and NaN -> 0 (Sec. 3).
-__device__ __forceinline__ unsigned sign_bits8(uint4 w, float &asum) {
-    unsigned bits = 0;
-    const unsigned dw[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        float lo = __uint_as_float(dw[i] << 16);
-        float hi = __uint_as_float(dw[i] & 0xffff0000u);
-        bits |= (lo >= 0.0f ? 1u : 0u) << (2 * i);
-        bits |= (hi >= 0.0f ? 1u : 0u) << (2 * i + 1);
-        asum += fabsf(lo) + fabsf(hi);
-    }
-    return bits;
-}
-
-typedef unsigned u4p __attribute__((ext_vector_type(4)));
+typedef u4 u4p;
 
 struct PackSide {
     const uint16_t *x;
@@ -67,7 +52,7 @@ __device__ __forceinline__ float pack_tile(const uint16_t *__restrict__ xb, int6
         const int e = threadIdx.x + k * PACK_THREADS;
         if (e < ntok * C16)
             bytes[(e / C16) * (4 * W) + (e % C16)] =
-                (uint8_t)sign_bits8(make_uint4(v[k][0], v[k][1], v[k][2], v[k][3]), asum);
+                (uint8_t)sign_bits8_abs(v[k], asum);
     }
     __syncthreads();
     for (int i = threadIdx.x; i < ntok * W; i += PACK_THREADS) ob[i] = words[i];
@@ -133,7 +118,7 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_stream_kernel(PackSide q, P
         for (int u = 0; u < U; ++u) {
             const int tok = base + u * 4 * TPW + tl;
             const bool on = lane_on && tok < tend;
-            unsigned bits = sign_bits8(make_uint4(v[u][0], v[u][1], v[u][2], v[u][3]), asum);
+            unsigned bits = sign_bits8_abs(v[u], asum);
             bits = on ? bits : 0u;  // padding bits are 0
             const unsigned word = quad_bcast<0>(bits) | (quad_bcast<1>(bits) << 8) |
                                   (quad_bcast<2>(bits) << 16) | (quad_bcast<3>(bits) << 24);

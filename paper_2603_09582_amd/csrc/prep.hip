@@ -13,14 +13,6 @@ namespace binattn {
 
 constexpr int PREP_THREADS = 256;
 
-// 8 sign bits -> 8 FP4 (e2m1) nibbles: +1.0 (0x2) where set, -1.0 (0xA) where clear.
-__device__ __forceinline__ unsigned fp4_pm1_bits8(unsigned b) {
-    unsigned x = (b | (b << 12)) & 0x000F000Fu;
-    x = (x | (x << 6)) & 0x03030303u;
-    x = (x | (x << 3)) & 0x11111111u;
-    return 0xAAAAAAAAu - (x << 3);
-}
-
 // Key block `blk` of one head: sign words -> FP4 rows of the block image.
 // One thread per (row position, sign word): 32 channels -> 16 bytes of FP4 codes.
 __device__ __forceinline__ void expand_k_block(const uint32_t *__restrict__ kb, int N, int d, int W,
@@ -35,7 +27,7 @@ __device__ __forceinline__ void expand_k_block(const uint32_t *__restrict__ kb, 
         u4 o;
 #pragma unroll
         for (int n = 0; n < 4; ++n)
-            o[n] = (8 * n < valid) ? fp4_pm1_bits8((word >> (8 * n)) & 0xFFu) : 0u;
+            o[n] = (8 * n < valid) ? fp4_pm1_from_bits8((word >> (8 * n)) & 0xFFu) : 0u;
         *reinterpret_cast<u4 *>(dst + (int64_t)pos * KP + 16 * k_chunk(pos, w, KP)) = o;
     }
 }
