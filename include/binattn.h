@@ -47,7 +47,9 @@ enum {
     BINATTN_ERR_DTYPE = -6,     /* unknown bias dtype                              */
     BINATTN_ERR_LAUNCH = -7,    /* the HIP runtime refused a launch                */
     BINATTN_ERR_VARIANT = -8,   /* unknown logits variant                          */
-    BINATTN_ERR_RANGE = -9      /* row range outside [0, N]                        */
+    BINATTN_ERR_RANGE = -9,     /* row range outside [0, N]                        */
+    BINATTN_ERR_TOO_LARGE = -10, /* shape needs more than the static scratch holds (binattn_forward_static) */
+    BINATTN_ERR_DEVICE = -11    /* current device / static buffer could not be resolved */
 };
 
 enum { BINATTN_BIAS_BF16 = 1, BINATTN_BIAS_F32 = 2 };
@@ -166,6 +168,27 @@ int binattn_forward(const uint32_t *q_bits, const uint32_t *k_bits, const float 
                     float scale, int B, int H, int N, int d, void *out,
                     const int64_t out_strides[3], void *workspace, size_t workspace_bytes,
                     unsigned flags, void *stream);
+
+/*
+ * binattn_forward for callers that cannot allocate device memory or carry a workspace around:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and results as binattn_forward, without the workspace: the operand images,
+ * delta_v and the V absmax partials live in a buffer of BINATTN_STATIC_SCRATCH_BYTES that is
+ * part of the library's device code (one copy per GPU, held until the process ends).  The call
+ * allocates and frees nothing.
+ *  - A shape with binattn_workspace_bytes(B, H, N, d) > BINATTN_STATIC_SCRATCH_BYTES returns
+ *    BINATTN_ERR_TOO_LARGE and launches nothing (the five benchmark workloads fit).
+ *  - Every call on a GPU uses that GPU's one buffer and overwrites all of it that it reads, so
+ *    nothing needs clearing between calls; calls that overlap in time on one GPU (different
+ *    streams, or several host threads) race on it and must be ordered by the caller.
+ *  - The first call on a device looks the buffer's address up (no allocation, but a runtime
+ *    query): make it outside a stream capture.
+ */
+#define BINATTN_STATIC_SCRATCH_BYTES (64u << 20)
+int binattn_forward_static(const uint32_t *q_bits, const uint32_t *k_bits, const float *mu_q,
+                           const float *mu_k, const void *v, const int64_t v_strides[3], const void *bias,
+                           int bias_dtype, const int64_t bias_strides[3], float scale, int B, int H, int N,
+                           int d, void *out, const int64_t out_strides[3], unsigned flags, void *stream);
 
 /* binattn_prepare_kv followed by binattn_attend_axial. */
 int binattn_forward_axial(const uint32_t *q_bits, const uint32_t *k_bits, const float *mu_q,

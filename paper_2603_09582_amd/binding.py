@@ -22,7 +22,7 @@ LOGITS_POPCOUNT, LOGITS_MFMA_I8, LOGITS_MFMA_FP4 = 0, 1, 2
 EXPORTS = ["binattn_version", "binattn_strerror", "binattn_pack_qk", "binattn_workspace_bytes",
            "binattn_prepare_kv", "binattn_attend", "binattn_forward", "binattn_attend_axial",
            "binattn_forward_axial", "binattn_attend_relpos", "binattn_forward_relpos", "binattn_forward_fused",
-           "binattn_forward_fused_relpos",
+           "binattn_forward_fused_relpos", "binattn_forward_static",
            "binattn_logits_debug", "binattn_quant_v_debug"]
 
 _lib = None
@@ -58,6 +58,9 @@ def lib():
     L.binattn_forward.argtypes = [vp, vp, vp, vp, vp, i64p, vp, C.c_int, i64p, C.c_float,
                                   C.c_int, C.c_int, C.c_int, C.c_int, vp, i64p, vp, C.c_size_t,
                                   C.c_uint, vp]
+    L.binattn_forward_static.restype = C.c_int
+    L.binattn_forward_static.argtypes = [vp, vp, vp, vp, vp, i64p, vp, C.c_int, i64p, C.c_float,
+                                         C.c_int, C.c_int, C.c_int, C.c_int, vp, i64p, C.c_uint, vp]
     L.binattn_prepare_kv.restype = C.c_int
     L.binattn_prepare_kv.argtypes = [vp, vp, i64p, C.c_int, C.c_int, C.c_int, C.c_int, vp,
                                      C.c_size_t, vp]
@@ -282,6 +285,25 @@ def forward(q_bits: torch.Tensor, k_bits: torch.Tensor, mu_q: Optional[torch.Ten
         out.data_ptr(), _strides3(out), workspace.data_ptr(), workspace.numel(), int(flags),
         _stream())
     _check(rc, "binattn_forward")
+    return out
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def forward_static(q_bits: torch.Tensor, k_bits: torch.Tensor, mu_q: Optional[torch.Tensor],
+                   mu_k: Optional[torch.Tensor], v: torch.Tensor, bias: Optional[torch.Tensor],
+                   scale: float, out: torch.Tensor, flags: int = 0) -> torch.Tensor:
+    """binattn_forward_static: binattn_forward on the library's own static scratch.  `out` is
+    the caller's (this wrapper allocates nothing either)."""
+    B, H, N, d = v.shape
+    bptr, bdt, bst = _bias_args(bias)
+    rc = lib().binattn_forward_static(
+        q_bits.data_ptr(), k_bits.data_ptr(),
+        None if mu_q is None else mu_q.data_ptr(), None if mu_k is None else mu_k.data_ptr(),
+        v.data_ptr(), _strides3(v), bptr, bdt, bst, float(scale), B, H, N, d,
+        out.data_ptr(), _strides3(out), int(flags), _stream())
+    _check(rc, "binattn_forward_static")
     return out
 
 

@@ -2,7 +2,14 @@
 // the launch sequences.  See include/binattn.h for the contract.
 #include "binattn_internal.h"
 
+#include <mutex>
+
 using namespace binattn;
+
+// Scratch of binattn_forward_static: one array per GPU, held from the moment the library's
+// code is loaded on that GPU until the process ends.  In host code this name only stands for
+// the symbol; the device address is looked up once per device (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[BINATTN_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -33,11 +40,40 @@ int check_workspace(const void *ws, size_t bytes, const Workspace &w) {
     return BINATTN_OK;
 }
 
+// Arguments common to the binattn_forward* entry points (everything but bias and workspace).
+int check_forward_args(const uint32_t *q_bits, const uint32_t *k_bits, const float *mu_q, const float *mu_k,
+                       const void *v, const int64_t v_strides[3], const void *out,
+                       const int64_t out_strides[3], int B, int H, int N, int d) {
+    if (!q_bits || !k_bits || !v || !out) return BINATTN_ERR_NULL;
+    if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
+    const Shape s = make_shape(B, H, N, d);
+    Strides3 tmp;
+    int rc;
+    if ((rc = check_strides_bhnd(v_strides, s, &tmp)) != BINATTN_OK) return rc;
+    if ((rc = check_strides_bhnd(out_strides, s, &tmp)) != BINATTN_OK) return rc;
+    if (!aligned(v, 16) || !aligned(out, 16) || !aligned(q_bits, 4) || !aligned(k_bits, 4))
+        return BINATTN_ERR_ALIGN;
+    if ((mu_q && !aligned(mu_q, 4)) || (mu_k && !aligned(mu_k, 4))) return BINATTN_ERR_ALIGN;
+    return BINATTN_OK;
+}
+
+// A dense bias argument (ignored when absent or switched off by the flag).
+int check_dense_bias(const void *bias, int bias_dtype, const int64_t bias_strides[3], int N, unsigned flags) {
+    if (bias == nullptr || (flags & BINATTN_FLAG_NO_BIAS)) return BINATTN_OK;
+    if (bias_dtype != BINATTN_BIAS_BF16 && bias_dtype != BINATTN_BIAS_F32) return BINATTN_ERR_DTYPE;
+    if (!bias_strides) return BINATTN_ERR_NULL;
+    for (int i = 0; i < 3; ++i)
+        if (bias_strides[i] < 0) return BINATTN_ERR_STRIDE;
+    if (N > 1 && bias_strides[2] < N) return BINATTN_ERR_STRIDE;
+    if (!aligned(bias, bias_dtype == BINATTN_BIAS_BF16 ? 2 : 4)) return BINATTN_ERR_ALIGN;
+    return BINATTN_OK;
+}
+
 }  // namespace
 
 extern "C" {
 
-int binattn_version(void) { return 131; }
+int binattn_version(void) { return 140; }
 
 const char *binattn_strerror(int code) {
     switch (code) {
@@ -51,6 +87,8 @@ const char *binattn_strerror(int code) {
         case BINATTN_ERR_LAUNCH: return "HIP runtime refused the launch";
         case BINATTN_ERR_VARIANT: return "unknown logits variant";
         case BINATTN_ERR_RANGE: return "row range outside [0, N]";
+        case BINATTN_ERR_TOO_LARGE: return "the shape needs more scratch than the library's static buffer holds";
+        case BINATTN_ERR_DEVICE: return "the HIP runtime could not name the current device or the static buffer";
         default: return "unknown error code";
     }
 }
@@ -280,29 +318,56 @@ int binattn_forward(const uint32_t *q_bits, const uint32_t *k_bits, const float 
                     int d, void *out, const int64_t out_strides[3], void *workspace,
                     size_t workspace_bytes, unsigned flags, void *stream) {
     // Validate the second stage's arguments before the first stage launches anything.
-    if (!q_bits || !k_bits || !v || !out) return BINATTN_ERR_NULL;
-    if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
-    const Shape s = make_shape(B, H, N, d);
-    Strides3 tmp;
-    int rc;
-    if ((rc = check_strides_bhnd(v_strides, s, &tmp)) != BINATTN_OK) return rc;
-    if ((rc = check_strides_bhnd(out_strides, s, &tmp)) != BINATTN_OK) return rc;
-    if (!aligned(v, 16) || !aligned(out, 16) || !aligned(q_bits, 4) || !aligned(k_bits, 4))
-        return BINATTN_ERR_ALIGN;
-    if ((mu_q && !aligned(mu_q, 4)) || (mu_k && !aligned(mu_k, 4))) return BINATTN_ERR_ALIGN;
-    if (bias != nullptr && !(flags & BINATTN_FLAG_NO_BIAS)) {
-        if (bias_dtype != BINATTN_BIAS_BF16 && bias_dtype != BINATTN_BIAS_F32) return BINATTN_ERR_DTYPE;
-        if (!bias_strides) return BINATTN_ERR_NULL;
-        for (int i = 0; i < 3; ++i)
-            if (bias_strides[i] < 0) return BINATTN_ERR_STRIDE;
-        if (N > 1 && bias_strides[2] < N) return BINATTN_ERR_STRIDE;
-        if (!aligned(bias, bias_dtype == BINATTN_BIAS_BF16 ? 2 : 4)) return BINATTN_ERR_ALIGN;
-    }
+    int rc = check_forward_args(q_bits, k_bits, mu_q, mu_k, v, v_strides, out, out_strides, B, H, N, d);
+    if (rc != BINATTN_OK) return rc;
+    if ((rc = check_dense_bias(bias, bias_dtype, bias_strides, N, flags)) != BINATTN_OK) return rc;
     if ((rc = binattn_prepare_kv(k_bits, v, v_strides, B, H, N, d, workspace, workspace_bytes,
                                  stream)) != BINATTN_OK)
         return rc;
     return binattn_attend(q_bits, mu_q, mu_k, bias, bias_dtype, bias_strides, scale, B, H, N, d, out,
                           out_strides, workspace, workspace_bytes, flags, stream);
+}
+
+}  // extern "C" (reopened below)
+
+namespace {
+// Device address of `scratch` on the current device, looked up on the first call there.
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[MAX_DEVICES] = {};
+
+int static_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return BINATTN_ERR_DEVICE;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+            (void)hipGetLastError();
+            return BINATTN_ERR_DEVICE;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return BINATTN_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int binattn_forward_static(const uint32_t *q_bits, const uint32_t *k_bits, const float *mu_q,
+                           const float *mu_k, const void *v, const int64_t v_strides[3], const void *bias,
+                           int bias_dtype, const int64_t bias_strides[3], float scale, int B, int H, int N,
+                           int d, void *out, const int64_t out_strides[3], unsigned flags, void *stream) {
+    int rc = check_forward_args(q_bits, k_bits, mu_q, mu_k, v, v_strides, out, out_strides, B, H, N, d);
+    if (rc != BINATTN_OK) return rc;
+    if ((rc = check_dense_bias(bias, bias_dtype, bias_strides, N, flags)) != BINATTN_OK) return rc;
+    const size_t need = make_workspace(make_shape(B, H, N, d)).total;
+    if (need > (size_t)BINATTN_STATIC_SCRATCH_BYTES) return BINATTN_ERR_TOO_LARGE;
+    void *ptr = nullptr;
+    if ((rc = static_scratch(&ptr)) != BINATTN_OK) return rc;
+    return binattn_forward(q_bits, k_bits, mu_q, mu_k, v, v_strides, bias, bias_dtype, bias_strides, scale, B,
+                           H, N, d, out, out_strides, ptr, (size_t)BINATTN_STATIC_SCRATCH_BYTES, flags, stream);
 }
 
 int binattn_forward_axial(const uint32_t *q_bits, const uint32_t *k_bits, const float *mu_q,
@@ -311,16 +376,8 @@ int binattn_forward_axial(const uint32_t *q_bits, const uint32_t *k_bits, const 
                           int H, int N, int d, void *out, const int64_t out_strides[3], void *workspace,
                           size_t workspace_bytes, unsigned flags, void *stream) {
     // Validate the second stage's arguments before the first stage launches anything.
-    if (!q_bits || !k_bits || !v || !out) return BINATTN_ERR_NULL;
-    if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
-    const Shape s = make_shape(B, H, N, d);
-    Strides3 tmp;
-    int rc;
-    if ((rc = check_strides_bhnd(v_strides, s, &tmp)) != BINATTN_OK) return rc;
-    if ((rc = check_strides_bhnd(out_strides, s, &tmp)) != BINATTN_OK) return rc;
-    if (!aligned(v, 16) || !aligned(out, 16) || !aligned(q_bits, 4) || !aligned(k_bits, 4))
-        return BINATTN_ERR_ALIGN;
-    if ((mu_q && !aligned(mu_q, 4)) || (mu_k && !aligned(mu_k, 4))) return BINATTN_ERR_ALIGN;
+    int rc = check_forward_args(q_bits, k_bits, mu_q, mu_k, v, v_strides, out, out_strides, B, H, N, d);
+    if (rc != BINATTN_OK) return rc;
     const AxialBias ax = {bias_y, bias_x, Gy, Gx};
     if ((rc = check_axial(ax, N)) != BINATTN_OK) return rc;
     if ((rc = binattn_prepare_kv(k_bits, v, v_strides, B, H, N, d, workspace, workspace_bytes,
@@ -335,17 +392,10 @@ int binattn_forward_relpos(const uint32_t *q_bits, const uint32_t *k_bits, const
                            const float *table, int Gy, int Gx, float scale, int B, int H, int N, int d,
                            void *out, const int64_t out_strides[3], void *workspace,
                            size_t workspace_bytes, unsigned flags, void *stream) {
+    if (!table) return BINATTN_ERR_NULL;
     // Validate the second stage's arguments before the first stage launches anything.
-    if (!q_bits || !k_bits || !v || !out || !table) return BINATTN_ERR_NULL;
-    if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
-    const Shape s = make_shape(B, H, N, d);
-    Strides3 tmp;
-    int rc;
-    if ((rc = check_strides_bhnd(v_strides, s, &tmp)) != BINATTN_OK) return rc;
-    if ((rc = check_strides_bhnd(out_strides, s, &tmp)) != BINATTN_OK) return rc;
-    if (!aligned(v, 16) || !aligned(out, 16) || !aligned(q_bits, 4) || !aligned(k_bits, 4))
-        return BINATTN_ERR_ALIGN;
-    if ((mu_q && !aligned(mu_q, 4)) || (mu_k && !aligned(mu_k, 4))) return BINATTN_ERR_ALIGN;
+    int rc = check_forward_args(q_bits, k_bits, mu_q, mu_k, v, v_strides, out, out_strides, B, H, N, d);
+    if (rc != BINATTN_OK) return rc;
     AxialBias ax = {nullptr, nullptr, Gy, Gx};
     ax.table = table;
     if ((rc = check_axial(ax, N)) != BINATTN_OK) return rc;

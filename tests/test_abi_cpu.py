@@ -27,7 +27,7 @@ def test_library_loads_and_exports_every_declared_symbol():
         assert hasattr(L, n), n
     assert L.binattn_version() >= 100
     assert L.binattn_strerror(0) == b"ok"
-    for code in range(-9, 0):
+    for code in range(-11, 0):
         assert len(L.binattn_strerror(code)) > 3
 
 
@@ -199,3 +199,24 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode == 2
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_forward_static_rejects_bad_arguments_before_touching_the_device():
+    L = ba.lib()
+
+    def call(qb=FAKE, v=FAKE, out=FAKE, B=1, H=2, N=16, d=64, bias=None, bdt=1, bs=None):
+        vs = st(H * N * d, N * d, d)
+        return L.binattn_forward_static(qb, FAKE, FAKE, FAKE, v, vs, bias, bdt, bs, 0.125, B, H, N, d, out,
+                                        vs, 0, None)
+
+    assert call(qb=None) == -1 and call(out=None) == -1
+    assert call(d=20) == -2 and call(N=0) == -2
+    assert call(v=FAKE + 8) == -4
+    assert call(bias=FAKE, bdt=9, bs=st(0, 256, 16)) == -6
+    # a shape whose workspace exceeds the static scratch: refused, nothing launched
+    assert ba.workspace_bytes(8, 16, 16384, 64) > ba.STATIC_SCRATCH_BYTES
+    assert call(B=8, H=16, N=16384, d=64) == -10
+    assert b"static" in L.binattn_strerror(-10)
+    # the five benchmark workloads fit
+    for (B, H, N, d) in [(1, 3, 197, 64), (64, 12, 197, 64), (32, 16, 256, 72), (8, 16, 1024, 72), (2, 16, 16384, 64)]:
+        assert 0 < ba.workspace_bytes(B, H, N, d) <= ba.STATIC_SCRATCH_BYTES
