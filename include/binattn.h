@@ -57,15 +57,24 @@ enum { BINATTN_BIAS_BF16 = 1, BINATTN_BIAS_F32 = 2 };
 /* flags of binattn_forward */
 enum {
     BINATTN_FLAG_NO_MU = 1,   /* ignore mu_q, mu_k (ablation row "no scale", Tab. 5) */
-    BINATTN_FLAG_NO_BIAS = 2  /* ignore bias (ablation rows without bias, Tab. 5)    */
+    BINATTN_FLAG_NO_BIAS = 2, /* ignore bias (ablation rows without bias, Tab. 5)    */
+    BINATTN_FLAG_LUT = 4      /* bias-free calls only: read 255 exp(S - m) from a per-head table
+                                 of its d + 1 possible values instead of computing every
+                                 exponential.  Same results up to the rounding of one fp32
+                                 exponential; measured slower than the exponentials on MI355X
+                                 (the table read costs more than the FMA + v_exp_f32 it
+                                 replaces), so it is opt-in and kept for comparison         */
 };
 
 /* variants of binattn_logits_debug */
 enum {
     BINATTN_LOGITS_POPCOUNT = 0, /* d - 2*popcount(q XOR k) on the vector ALU (Sec. 4.1)   */
     BINATTN_LOGITS_MFMA_I8 = 1,  /* +-1 int8 contraction on the matrix cores                */
-    BINATTN_LOGITS_MFMA_FP4 = 2  /* +-1.0 FP4 contraction, fp32 accumulate (exact); the form
+    BINATTN_LOGITS_MFMA_FP4 = 2, /* +-1.0 FP4 contraction, fp32 accumulate (exact); the form
                                     the fused kernel uses                                   */
+    BINATTN_LOGITS_ROWSUM = 0x100 /* OR-ed to a variant: write sum_j I_ij per query row, int32
+                                    [B, H, row_end - row_begin], instead of the matrix (no
+                                    4-byte-per-pair store stream: the form for timing)      */
 };
 
 int binattn_version(void);
@@ -256,6 +265,21 @@ int binattn_logits_debug(const uint32_t *q_bits, const uint32_t *k_bits, int B, 
 int binattn_quant_v_debug(const void *v, const int64_t v_strides[3], int B, int H, int N, int d,
                           int8_t *vq, float *delta, void *workspace, size_t workspace_bytes,
                           void *stream);
+
+/*
+ * Measurement aid, not part of the attention path: runs `blocks` workgroups of 256 lanes,
+ * each lane issuing 8 * iters instructions of ONE kind (BINATTN_PROBE_*) in eight independent
+ * chains, and writes one float per lane to `out` (blocks * 256 floats).  Timing the launch
+ * gives the chip's issue rate for that instruction: the roofline of the fused kernel counts
+ * vector-ALU issue slots per (query, key) pair, and this is how the slots of v_exp_f32 (two)
+ * and of the others (one) were measured.  BINATTN_PROBE_CVT_PK_U8 issues two instructions per
+ * step (the conversion and an OR).  iters, blocks >= 1.
+ */
+enum {
+    BINATTN_PROBE_FMA = 0, BINATTN_PROBE_EXP2 = 1, BINATTN_PROBE_ADD = 2, BINATTN_PROBE_MAX3 = 3,
+    BINATTN_PROBE_CVT_PK_U8 = 4, BINATTN_PROBE_CVT_F32_I32 = 5
+};
+int binattn_probe_valu(int op, int iters, int blocks, float *out, void *stream);
 
 #ifdef __cplusplus
 }

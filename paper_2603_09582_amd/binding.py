@@ -16,13 +16,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbinattn.so")
 
 BIAS_BF16, BIAS_F32 = 1, 2
-FLAG_NO_MU, FLAG_NO_BIAS = 1, 2
+FLAG_NO_MU, FLAG_NO_BIAS, FLAG_LUT = 1, 2, 4
 LOGITS_POPCOUNT, LOGITS_MFMA_I8, LOGITS_MFMA_FP4 = 0, 1, 2
+LOGITS_ROWSUM = 0x100
 
 EXPORTS = ["binattn_version", "binattn_strerror", "binattn_pack_qk", "binattn_workspace_bytes",
            "binattn_prepare_kv", "binattn_attend", "binattn_forward", "binattn_attend_axial",
            "binattn_forward_axial", "binattn_attend_relpos", "binattn_forward_relpos", "binattn_forward_fused",
-           "binattn_forward_fused_relpos", "binattn_forward_static",
+           "binattn_forward_fused_relpos", "binattn_forward_static", "binattn_probe_valu",
            "binattn_logits_debug", "binattn_quant_v_debug"]
 
 _lib = None
@@ -61,6 +62,8 @@ def lib():
     L.binattn_forward_static.restype = C.c_int
     L.binattn_forward_static.argtypes = [vp, vp, vp, vp, vp, i64p, vp, C.c_int, i64p, C.c_float,
                                          C.c_int, C.c_int, C.c_int, C.c_int, vp, i64p, C.c_uint, vp]
+    L.binattn_probe_valu.restype = C.c_int
+    L.binattn_probe_valu.argtypes = [C.c_int, C.c_int, C.c_int, vp, vp]
     L.binattn_prepare_kv.restype = C.c_int
     L.binattn_prepare_kv.argtypes = [vp, vp, i64p, C.c_int, C.c_int, C.c_int, C.c_int, vp,
                                      C.c_size_t, vp]
@@ -346,8 +349,9 @@ def forward_fused_relpos(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, tabl
 def logits_debug(q_bits: torch.Tensor, k_bits: torch.Tensor, d: int, row_begin: int, row_end: int,
                  variant: int, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     B, H, N, _ = q_bits.shape
-    out = torch.empty(B, H, row_end - row_begin, N, dtype=torch.int32, device=q_bits.device)
-    if workspace is None and variant == LOGITS_MFMA_FP4:
+    shape = (B, H, row_end - row_begin) if variant & LOGITS_ROWSUM else (B, H, row_end - row_begin, N)
+    out = torch.empty(shape, dtype=torch.int32, device=q_bits.device)
+    if workspace is None and (variant & ~LOGITS_ROWSUM) == LOGITS_MFMA_FP4:
         workspace = alloc_workspace(B, H, N, d, q_bits.device)
     rc = lib().binattn_logits_debug(
         q_bits.data_ptr(), k_bits.data_ptr(), B, H, N, d, row_begin, row_end, out.data_ptr(),
@@ -355,6 +359,16 @@ def logits_debug(q_bits: torch.Tensor, k_bits: torch.Tensor, d: int, row_begin: 
         0 if workspace is None else workspace.numel(), _stream())
     _check(rc, "binattn_logits_debug")
     return out
+
+
+PROBE_OPS = {"fma": 0, "exp2": 1, "add": 2, "max3": 3, "cvt_pk_u8+or": 4, "cvt_f32_i32": 5}
+PROBE_CHAINS = 8
+
+
+def probe_valu(op: int, iters: int, blocks: int, out: torch.Tensor) -> None:
+    """binattn_probe_valu: the issue-rate probe (a measurement aid, see include/binattn.h)."""
+    assert out.dtype == torch.float32 and out.numel() >= blocks * 256
+    _check(lib().binattn_probe_valu(op, iters, blocks, out.data_ptr(), _stream()), "binattn_probe_valu")
 
 
 def quant_v_debug(v: torch.Tensor, workspace: Optional[torch.Tensor] = None):

@@ -182,7 +182,8 @@ int attend_impl(const uint32_t *q_bits, const float *mu_q, const float *mu_k, co
 
     const bool no_bias = (flags & BINATTN_FLAG_NO_BIAS) != 0;
     const bool use_bias = bias != nullptr && !no_bias;
-    int mode = BIAS_NONE;
+    // without a bias BINATTN_FLAG_LUT reads the exponentials from a per-head table
+    int mode = (flags & BINATTN_FLAG_LUT) ? BIAS_LUT : BIAS_NONE;
     Strides3 bs = {0, 0, 0};
     int gx_shift = 0;
     bool wide_rows2 = false;
@@ -463,6 +464,8 @@ int binattn_logits_debug(const uint32_t *q_bits, const uint32_t *k_bits, int B, 
     if (!q_bits || !k_bits || !logits) return BINATTN_ERR_NULL;
     if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
     if (row_begin < 0 || row_end < row_begin || row_end > N) return BINATTN_ERR_RANGE;
+    const bool rowsum = (variant & BINATTN_LOGITS_ROWSUM) != 0;
+    variant &= ~BINATTN_LOGITS_ROWSUM;
     if (variant != BINATTN_LOGITS_POPCOUNT && variant != BINATTN_LOGITS_MFMA_I8 &&
         variant != BINATTN_LOGITS_MFMA_FP4)
         return BINATTN_ERR_VARIANT;
@@ -470,15 +473,15 @@ int binattn_logits_debug(const uint32_t *q_bits, const uint32_t *k_bits, int B, 
     const Shape s = make_shape(B, H, N, d);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (variant == BINATTN_LOGITS_POPCOUNT)
-        return launch_logits_popcount(q_bits, k_bits, s, row_begin, row_end, logits, st);
+        return launch_logits_popcount(q_bits, k_bits, s, row_begin, row_end, logits, rowsum, st);
     if (variant == BINATTN_LOGITS_MFMA_I8)
-        return launch_logits_i8(q_bits, k_bits, s, row_begin, row_end, logits, st);
+        return launch_logits_i8(q_bits, k_bits, s, row_begin, row_end, logits, rowsum, st);
     const Workspace w = make_workspace(s);
     int rc;
     if ((rc = check_workspace(workspace, workspace_bytes, w)) != BINATTN_OK) return rc;
     char *ws = static_cast<char *>(workspace);
     if ((rc = launch_expand_k(k_bits, s, ws, w, st)) != BINATTN_OK) return rc;
-    return launch_logits_fp4(q_bits, ws, w, s, row_begin, row_end, logits, st);
+    return launch_logits_fp4(q_bits, ws, w, s, row_begin, row_end, logits, rowsum, st);
 }
 
 int binattn_quant_v_debug(const void *v, const int64_t v_strides[3], int B, int H, int N, int d,
@@ -497,6 +500,13 @@ int binattn_quant_v_debug(const void *v, const int64_t v_strides[3], int B, int 
     char *ws = static_cast<char *>(workspace);
     if ((rc = launch_prepare(v, vs, nullptr, s, ws, w, st)) != BINATTN_OK) return rc;
     return launch_export_vq(s, ws, w, vq, delta, st);
+}
+
+int binattn_probe_valu(int op, int iters, int blocks, float *out, void *stream) {
+    if (!out) return BINATTN_ERR_NULL;
+    if (iters < 1 || blocks < 1 || blocks > (1 << 20)) return BINATTN_ERR_SHAPE;
+    if (!aligned(out, 4)) return BINATTN_ERR_ALIGN;
+    return launch_probe_valu(op, iters, blocks, out, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -131,11 +131,13 @@ int launch_prepare(const void *v, Strides3 vs, const uint32_t *k_bits, const Sha
 int launch_export_vq(const Shape &s, const char *ws, const Workspace &w, int8_t *vq, float *delta,
                      hipStream_t stream);
 int launch_logits_popcount(const uint32_t *q_bits, const uint32_t *k_bits, const Shape &s,
-                           int row_begin, int row_end, int32_t *logits, hipStream_t stream);
+                           int row_begin, int row_end, int32_t *logits, bool rowsum, hipStream_t stream);
 int launch_logits_fp4(const uint32_t *q_bits, const char *ws, const Workspace &w, const Shape &s,
-                      int row_begin, int row_end, int32_t *logits, hipStream_t stream);
+                      int row_begin, int row_end, int32_t *logits, bool rowsum, hipStream_t stream);
 int launch_logits_i8(const uint32_t *q_bits, const uint32_t *k_bits, const Shape &s, int row_begin,
-                     int row_end, int32_t *logits, hipStream_t stream);
+                     int row_end, int32_t *logits, bool rowsum, hipStream_t stream);
+
+int launch_probe_valu(int op, int iters, int blocks, float *out, hipStream_t stream);
 
 enum BiasMode {
     BIAS_NONE = 0,
@@ -143,7 +145,8 @@ enum BiasMode {
     BIAS_F32_VEC = 3,   // fp32 bias, 16-byte loads at use
     BIAS_BF16_LDS = 5,  // rows 16-byte aligned, N % 8 == 0: tile staged global -> LDS asynchronously
     BIAS_AXIAL = 7,     // b_ij = y[iy - jy] + x[ix - jx] on a Gy x Gx token grid, tables held in LDS
-    BIAS_TABLE = 9      // b_ij = t[iy - jy][ix - jx]: the full relative-position table of the head in LDS
+    BIAS_TABLE = 9,     // b_ij = t[iy - jy][ix - jx]: the full relative-position table of the head in LDS
+    BIAS_LUT = 11       // no bias: 255 exp(S - m) read from a per-head table indexed by (m - I) / 2
 };
 
 // largest grid side of BIAS_AXIAL (the tables of one head live in LDS)

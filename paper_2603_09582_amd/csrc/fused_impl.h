@@ -128,6 +128,16 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     constexpr bool TABLE = MODE == BIAS_TABLE;
     constexpr int TBP = 2 * TABLE_MAX_G + 16;
     __shared__ float tab2[TABLE ? (2 * TABLE_MAX_G - 1) * TBP : 4];
+    // BIAS_LUT (no bias): the logit takes only the d + 1 values alpha * I, I = d, d - 2, ..., -d, and
+    // the running maximum is one of them, so 255 * exp(S - m) is one of d + 1 numbers that depend
+    // on the head alone: lut[k] = 255 * exp(-2 alpha k) for m - I = 2 k.  Entries d + 1 ... 2 d + 1
+    // are 0: keys past the end of the sequence are given the "logit" I = -3 d - 2, below every
+    // real one and at most 2 d + 1 table steps under any running maximum.  The exponential and
+    // its argument disappear from the per-pair work; what remains is one address addition and
+    // one LDS read.
+    constexpr bool LUT = MODE == BIAS_LUT;
+    constexpr int LUTN = 264;
+    __shared__ float lut[LUT ? LUTN : 4];
     // delta_v of the current item (two copies: consecutive items alternate)
     __shared__ __attribute__((aligned(16))) float sdelta[2][NIMG][DKP];
 
@@ -199,6 +209,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     }
     int ax_ub = 0, ax_wb = 0;  // BIAS_AXIAL: this lane's window base in axu (floats), its y-table base
     float m_run, l_run, rho;  // running max (units of T = S / alpha), sum of 255 exp(S - m), rescale sum
+    int hb_run = 0x7fffffff;  // BIAS_LUT: running minimum of the bit patterns of 1.5 * 2^23 + (d - I)
     float Of[DK][16];         // output carry, channel 32 cb + 8 (r/4) + 4 g + r % 4
 
     // registers fetched ahead for the NEXT item
@@ -247,7 +258,15 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         const float a_abs = a_zero ? 1.0f : fabsf(alpha);
         inv_alpha = 1.0f / a_abs;
         a2 = a_abs * LOG2E_F;  // exponent multiplier in base 2
-        load_q_operand<DK2>(pend_q, d, g, a_neg, a_zero, qB);
+        // (BIAS_LUT lets the matrix core SUBTRACT the logit from a constant, see the block loop)
+        load_q_operand<DK2>(pend_q, d, g, LUT ? !a_neg : a_neg, a_zero, qB);
+        if (LUT) {
+            // (the previous item's last block is behind every wave; the barrier publishes the table)
+            for (int i = threadIdx.x; i < LUTN; i += FUSED_THREADS * NB)
+                lut[i] = i <= d ? __builtin_amdgcn_exp2f(fmaf(-2.0f * (float)i, a2, LOG2_255_F)) : 0.0f;
+            hb_run = 0x7fffffff;
+            __syncthreads();
+        }
         if (MODE == BIAS_BF16_VEC || MODE == BIAS_F32_VEC) brow = bias_row_ptr(t);
         if (LDS_BIAS) {
             bsrc = bias_dma_src(t);
@@ -506,6 +525,19 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
                 wt[t] = 0.0f;
                 T[t] = qk_mfma<DK2>(ka[t], qB, cin);
             }
+        } else if (LUT) {
+            // 1.5 * 2^23 + d - I: an integer in [0, 2 d] on top of the float-bit offset, so the bit
+            // pattern read as an integer is PV_MAGIC_BITS + (d - I) and all further logit
+            // arithmetic (minimum, table address) is integer arithmetic on it
+            const float cm = PV_MAGIC_F + (float)d;
+            v16f cin;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) cin[r] = cm;
+#pragma unroll
+            for (int t = 0; t < KT; ++t) {
+                wt[t] = 0.0f;
+                T[t] = qk_mfma<DK2>(ka[t], qB, cin);
+            }
         } else {
 #pragma unroll
             for (int t = 0; t < KT; ++t) {
@@ -536,14 +568,53 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
                 va[cb][t] = *reinterpret_cast<const v4i *>(ibuf + L::V_OFF + (32 * cb + m) * L::VP + 64 * g + 16 * t);
         }
 
-        if (it * BV + BV > N) {  // ragged last block: keys beyond N never count
+        const bool ragged = it * BV + BV > N;
+        if (ragged) {  // ragged last block: keys beyond N never count
 #pragma unroll
             for (int t = 0; t < KT; ++t)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    if (it * BV + 64 * g + 16 * t + r >= N) T[t][r] = -INFINITY;
+                    if (it * BV + 64 * g + 16 * t + r >= N)
+                        T[t][r] = LUT ? PV_MAGIC_F + (float)(4 * d + 2) : -INFINITY;
         }
 
+        float resc;
+        float ls0 = 0.0f, ls1 = 0.0f;
+        v4i pk[KT];
+        if constexpr (LUT) {
+            // 2. running maximum of I = running minimum of the bit patterns (a block always holds
+            //    a key inside the sequence, so the minimum is a real logit)
+            int hb = __float_as_int(T[0][0]);
+#pragma unroll
+            for (int t = 0; t < KT; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) hb = min(hb, __float_as_int(T[t][r]));
+            {
+                const auto sw2 = __builtin_amdgcn_permlane32_swap((unsigned)hb, (unsigned)hb, false, false);
+                hb = min((int)sw2[0], (int)sw2[1]);
+            }
+            const int hb_new = min(hb_run, hb);
+            // e^{m_old - m_new} with m = alpha (d - h): the first block of an item has nothing to carry
+            resc = hb_run == 0x7fffffff ? 0.0f : __builtin_amdgcn_exp2f((float)(hb_new - hb_run) * a2);
+            hb_run = hb_new;
+            // 3. 255 * exp(S - m) = lut[(h - h_min) / 2]: byte address 2 (h - h_min) past the table
+            const unsigned abase = lds_offset(lut) - 2u * (unsigned)hb_new;
+#pragma unroll
+            for (int t = 0; t < KT; ++t) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    unsigned w = 0;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const unsigned a = ((unsigned)__float_as_int(T[t][4 * i + j]) << 1) + abase;
+                        const float pe = *reinterpret_cast<const __attribute__((address_space(3))) float *>((size_t)a);
+                        if (j & 1) ls1 += pe; else ls0 += pe;
+                        w = __builtin_amdgcn_cvt_pk_u8_f32(pe, j, w);
+                    }
+                    pk[t][i] = (int)(w ^ 0x80808080u);
+                }
+            }
+        } else {
         // 2. running maximum (Alg. 1: m_ij = max(m_i,j-1, rowmax S_ij))
         float mx;
         if (AXIAL) {  // per-tile maxima, each shifted by the tile's y term
@@ -564,13 +635,11 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         }
         const float m_new = fmaxf(m_run, pair_max(mx));
         const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;  // whole row masked so far
-        const float resc = __builtin_amdgcn_exp2f((m_run - m_use) * a2);  // e^{m_old - m_new}
+        resc = __builtin_amdgcn_exp2f((m_run - m_use) * a2);  // e^{m_old - m_new}
         const float cexp = LOG2_255_F - m_use * a2;
         m_run = m_new;
 
         // 3. p = 255 * exp(S - m), its row sum, and the byte codes
-        float ls0 = 0.0f, ls1 = 0.0f;
-        v4i pk[KT];
 #pragma unroll
         for (int t = 0; t < KT; ++t) {
             const float ce = AXIAL ? fmaf(wt[t], a2, cexp) : cexp;
@@ -585,6 +654,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
                 }
                 pk[t][i] = (int)(w ^ 0x80808080u);  // code - 128 as signed bytes
             }
+        }
         }
         l_run = fmaf(l_run, resc, ls0 + ls1);
         rho = fmaf(rho, resc, 1.0f);
@@ -854,7 +924,7 @@ int launch_fused_dk(const FusedParams &p, int mode, hipStream_t stream) {
     }
     switch (mode) {
 #define CASE(M) case M: hipLaunchKernelGGL((fused_kernel<DK, M, 1>), grid, block, 0, stream, p); break;
-        CASE(BIAS_NONE) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC) CASE(BIAS_AXIAL) CASE(BIAS_TABLE)
+        CASE(BIAS_NONE) CASE(BIAS_LUT) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC) CASE(BIAS_AXIAL) CASE(BIAS_TABLE)
 #undef CASE
         case BIAS_BF16_LDS:
             if constexpr (DK <= 3) {
@@ -873,7 +943,7 @@ int launch_onehead_dk(const FusedParams &p, int mode, hipStream_t stream) {
     const dim3 grid((unsigned)needed), block(FUSED_THREADS * 2);
     switch (mode) {
 #define CASE(M) case M: hipLaunchKernelGGL((fused_kernel<DK, M, 2, WIDE_ONEHEAD>), grid, block, 0, stream, p); break;
-        CASE(BIAS_NONE) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC) CASE(BIAS_AXIAL) CASE(BIAS_TABLE)
+        CASE(BIAS_NONE) CASE(BIAS_LUT) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC) CASE(BIAS_AXIAL) CASE(BIAS_TABLE)
 #undef CASE
         case BIAS_BF16_LDS:
             if constexpr (DK <= 3) {

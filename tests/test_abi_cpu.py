@@ -220,3 +220,10 @@ def test_forward_static_rejects_bad_arguments_before_touching_the_device():
     # the five benchmark workloads fit
     for (B, H, N, d) in [(1, 3, 197, 64), (64, 12, 197, 64), (32, 16, 256, 72), (8, 16, 1024, 72), (2, 16, 16384, 64)]:
         assert 0 < ba.workspace_bytes(B, H, N, d) <= ba.STATIC_SCRATCH_BYTES
+
+
+def test_probe_rejects_bad_arguments():
+    L = ba.lib()
+    assert L.binattn_probe_valu(0, 16, 4, None, None) == -1
+    assert L.binattn_probe_valu(0, 0, 4, FAKE, None) == -2 and L.binattn_probe_valu(0, 16, 0, FAKE, None) == -2
+    assert L.binattn_probe_valu(0, 16, 4, FAKE + 2, None) == -4

@@ -168,6 +168,21 @@ def test_integer_logits_exact(B, H, N, d, variant):
             assert np.array_equal(got[b, h], want)
 
 
+@pytest.mark.parametrize("variant", [ba.LOGITS_POPCOUNT, ba.LOGITS_MFMA_I8, ba.LOGITS_MFMA_FP4])
+@pytest.mark.parametrize("B,H,N,d", [(1, 2, 197, 64), (2, 1, 300, 72), (1, 1, 1160, 128), (1, 2, 520, 32)])
+def test_integer_logit_row_sums_exact(B, H, N, d, variant):
+    # the row-sum forms of the three logit kernels (the ones that are timed against each other)
+    say(f"logit row sums variant={variant} B={B} H={H} N={N} d={d}")
+    x = small_inputs(B, H, N, d, 35 + N, extra="k_channel_offset")
+    qb, kb, _, _ = ba.pack_qk(dev(x.q), dev(x.k))
+    r0, r1 = 3, N - 2
+    got = ba.logits_debug(qb, kb, d, r0, r1, variant | ba.LOGITS_ROWSUM).cpu().numpy()
+    for b in range(B):
+        for h in range(H):
+            want = orc.logits_literal(np_bits(x.q[b, h]), np_bits(x.k[b, h]), rows=np.arange(r0, r1))
+            assert np.array_equal(got[b, h], want.sum(axis=1, dtype=np.int64).astype(np.int32))
+
+
 def run_forward(x, bias, flags=0, use_mu=True):
     q, k, v = dev(x.q), dev(x.k), dev(x.v)
     qb, kb, mq, mk = ba.pack_qk(q, k)
@@ -277,6 +292,53 @@ def test_forward_bias_modes_and_flags(kind):
     else:
         ref = oracle_forward(x, obias, use_mu=use_mu)["O2"]
     check_close(gpu_out_f64(out), ref, f"{kind}: out vs O2")
+
+
+@pytest.mark.parametrize("B,H,N,d", SHAPES)
+def test_forward_without_bias_table_path_and_exponential_path(B, H, N, d):
+    # Without a bias 255 exp(S - m) takes only d + 1 values per head: BINATTN_FLAG_LUT reads them
+    # from a table, the default computes every exponential.  Both against the oracle.
+    say(f"forward without bias B={B} H={H} N={N} d={d}")
+    x = small_inputs(B, H, N, d, 140 + N, extra="k_channel_offset")
+    ref = oracle_forward(x, None)["O2"]
+    alg = oracle_algorithm1(x, None, Bv=128)
+    lut = run_forward(x, None, flags=ba.FLAG_LUT)
+    exp = run_forward(x, None)
+    for got, what in ((lut, "table"), (exp, "exponentials")):
+        check_close(got, ref, f"no bias, {what}: out vs O2")
+        err = np.abs(got - alg)
+        say(f"    {what} vs Alg.1(Bv=128): max abs err {err.max():.3e}")
+        assert np.all(err <= 2e-3 + 2 ** -7 * np.abs(alg))
+
+
+@pytest.mark.parametrize("kind", ["negative_scale", "zero_scale", "large_scale", "no_mu", "fused", "fused_negative"])
+def test_table_path_scale_cases(kind):
+    B, H, N, d = 2, 2, 300, 72
+    say(f"table path: {kind}")
+    x = small_inputs(B, H, N, d, 171)
+    flags, use_mu = ba.FLAG_LUT, True
+    if kind in ("negative_scale", "fused_negative"):
+        x.scale = -x.scale
+    elif kind == "zero_scale":
+        x.scale = 0.0
+    elif kind == "large_scale":
+        x.scale = 2.5          # alpha ~ 1.6: the table falls to zero within a few entries
+    elif kind == "no_mu":
+        flags, use_mu = ba.FLAG_NO_MU | ba.FLAG_LUT, False
+    if kind.startswith("fused"):
+        x = small_inputs(B, H, 200, d, 172)
+        if kind == "fused_negative":
+            x.scale = -x.scale
+        out = ba.forward_fused(dev(x.q), dev(x.k), dev(x.v), None, x.scale, flags=ba.FLAG_LUT)
+        torch.cuda.synchronize()
+        got = gpu_out_f64(out)
+    else:
+        got = run_forward(x, None, flags=flags)
+    assert np.isfinite(got).all()
+    check_close(got, oracle_forward(x, None, use_mu=use_mu)["O2"], f"{kind}: out vs O2")
+    if kind == "large_scale":
+        alg = oracle_algorithm1(x, None, Bv=128)
+        assert np.all(np.abs(got - alg) <= 2e-3 + 2 ** -7 * np.abs(alg))
 
 
 def test_forward_null_mu_pointers_equal_no_mu_flag():
@@ -680,7 +742,7 @@ def test_forward_fused_more_heads_than_cus(layout):
 
 
 # ---- the five workloads, at full size, in the launch configuration bench.py times --------
-def _workload_check(name, heads=None, rows=None, rows_per_head=None, with_bias=True):
+def _workload_check(name, heads=None, rows=None, rows_per_head=None, with_bias=True, flags=0):
     """Run pack_qk + forward on workload `name` and compare with the oracle, head by head.
     heads: list of (b, h), None = every head.  rows: query rows checked on every head (None =
     all rows); rows_per_head(b, h) -> extra rows for that head.  Sign words, mu and outputs
@@ -689,7 +751,7 @@ def _workload_check(name, heads=None, rows=None, rows_per_head=None, with_bias=T
     N = w.N
     x = wl.make_inputs(w, device="cuda", with_bias=with_bias)
     qb, kb, mq, mk = ba.pack_qk(x.q, x.k)
-    out = ba.forward(qb, kb, mq, mk, x.v, x.bias, x.scale)
+    out = ba.forward(qb, kb, mq, mk, x.v, x.bias, x.scale, flags=flags)
     torch.cuda.synchronize()
     if heads is None:
         heads = [(b, h) for h in range(w.H) for b in range(w.B)]
@@ -766,15 +828,16 @@ def test_workload_vit_hires_every_head_sampled_rows():
                     rows_per_head=lambda b, h: np.random.default_rng(1000 + 16 * b + h).integers(0, N, 256))
 
 
-@pytest.mark.parametrize("name,with_bias", [("hd128_n4096", True), ("hd128_n16384", True), ("hd128_n32768", False)])
-def test_sweep_hd128_sampled_rows(name, with_bias):
+@pytest.mark.parametrize("name,with_bias,flags", [("hd128_n4096", True, 0), ("hd128_n16384", True, 0),
+                                                  ("hd128_n32768", False, 0), ("hd128_n32768", False, ba.FLAG_LUT)])
+def test_sweep_hd128_sampled_rows(name, with_bias, flags):
     # head dimension 128 (four channel blocks), the kernel-speed setting: with a dense bias
     # (8-wave row-pair workgroups, LDS bias tiles) and, at the longest length, without
     w = wl.WORKLOADS[name]
     N = w.N
     fixed = list(range(0, 16)) + list(range(N // 2 - 8, N // 2 + 8)) + list(range(N - 16, N))
     heads = [(0, 0), (w.B - 1, 15), (0, 7), (w.B - 1, 4)]
-    _workload_check(name, heads=sorted(set(heads)), rows=fixed, with_bias=with_bias,
+    _workload_check(name, heads=sorted(set(heads)), rows=fixed, with_bias=with_bias, flags=flags,
                     rows_per_head=lambda b, h: np.random.default_rng(50 + h).integers(0, N, 48))
 
 
