@@ -282,6 +282,17 @@ def config_row(name, steps=CONFIG_STEPS, warmup=CONFIG_WARMUP):
         _, cold = timed(lambda i: three_calls(ring[i % nset]), steps, nset)
         row["cold_cache"] = {"buffer_sets": nset, "bytes_per_set": per_set, "ms_per_step": med_min(cold)}
         del ring
+    if w.N > 256:     # the same step through the one-call entry point (binattn_attention: three launches)
+        one = lambda i: ba.attention(x.q, x.k, x.v, x.bias, x.scale, out=b.out, workspace=b.ws)
+        wall1, per1 = timed(one, steps, warmup)
+        # its first two launches read Q, K, V once (+ V a second time) and write the query sign
+        # words and the operand images
+        W = (w.d + 31) // 32
+        t_io = (4 * w.B * w.H * w.N * w.d * 2 + w.B * w.H * w.N * (W * 4 + w.d + 16 * W)) / (HBM_PEAK_GBS * 1e9) * 1e3
+        row["one_call"] = {"ms_per_step": med_min(per1), "ms_per_step_wall_mean": wall1,
+                           "tops_equiv": w.equiv_ops / (statistics.median(per1) * 1e-3) / 1e12,
+                           "t_bound_ms": bd["t_bound_fused_ms"] + t_io,
+                           "frac_of_bound": (bd["t_bound_fused_ms"] + t_io) / statistics.median(per1)}
     if w.N <= 256:    # the whole step as one launch (binattn_forward_fused)
         one = lambda i: ba.forward_fused(x.q, x.k, x.v, x.bias, x.scale, out=b.out)
         wall1, per1 = timed(one, steps, warmup)

@@ -233,6 +233,22 @@ int binattn_forward_fused(const void *q, const void *k, const void *v, const int
                           float *mu_k_out, unsigned flags, void *stream);
 
 /*
+ * The whole of Alg. 1 from the bf16 tensors, for any N: phi (Eq. 5), psi (Eq. 7) and the fused
+ * loop behind one call.  N <= 256 is binattn_forward_fused (one launch, workspace unused and
+ * may be NULL).  Longer sequences take three launches: one pass over Q, K, V that packs the
+ * query signs, writes the keys' +-1 operand rows directly (no key sign words in memory),
+ * and reduces the V absmax and the |q|, |k| sums per 256 tokens; the V quantisation, which
+ * also adds those partial sums in a fixed order (the abs-means are the same bits on every
+ * run, unlike binattn_pack_qk's atomics for N > 2048); and binattn_attend.
+ *   arguments as binattn_forward_fused, plus the workspace of binattn_workspace_bytes.
+ */
+int binattn_attention(const void *q, const void *k, const void *v, const int64_t q_strides[3],
+                      const int64_t k_strides[3], const int64_t v_strides[3], const void *bias, int bias_dtype,
+                      const int64_t bias_strides[3], float scale, int B, int H, int N, int d, void *out,
+                      const int64_t out_strides[3], float *mu_q_out, float *mu_k_out, void *workspace,
+                      size_t workspace_bytes, unsigned flags, void *stream);
+
+/*
  * binattn_forward_fused with the relative-position table of binattn_attend_relpos as bias
  * (table, Gy, Gx as there; Gy * Gx = N <= 256): for a 16 x 16 token grid the whole layer is
  * one launch and no [N, N] bias exists anywhere.

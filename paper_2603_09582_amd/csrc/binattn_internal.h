@@ -98,8 +98,12 @@ constexpr float PV_MAGIC_F = 12582912.0f;
 //   img   bytes [BH][nblk][Image<DK>::BYTES]
 //   delta f32   [BH][DKP]
 //   amax  f32   [BH][nchunk][DKP]           partial absmax of V
+// and, for the entry point that takes Q, K, V themselves:
+//   mu    f32   [2][BH]                     abs-means of Q and K
+//   psum  f32   [BH][nchunk][2]             their per-chunk partial sums
+//   qbits u32   [BH][N][W]                  query sign words
 struct Workspace {
-    size_t img, delta, amax, total;
+    size_t img, delta, amax, mu, psum, qbits, total;
     int img_bytes;
 };
 
@@ -112,6 +116,9 @@ inline Workspace make_workspace(const Shape &s) {
     w.img = off;   off = align256(off + (size_t)s.BH * s.nblk * w.img_bytes);
     w.delta = off; off = align256(off + (size_t)s.BH * s.DKP * 4);
     w.amax = off;  off = align256(off + (size_t)s.BH * s.nchunk * s.DKP * 4);
+    w.mu = off;    off = align256(off + (size_t)2 * s.BH * 4);
+    w.psum = off;  off = align256(off + (size_t)s.BH * s.nchunk * 2 * 4);
+    w.qbits = off; off = align256(off + (size_t)s.BH * s.N * s.W * 4);
     w.total = off;
     return w;
 }
@@ -128,6 +135,9 @@ int launch_expand_k(const uint32_t *k_bits, const Shape &s, char *ws, const Work
                     hipStream_t stream);
 int launch_prepare(const void *v, Strides3 vs, const uint32_t *k_bits, const Shape &s, char *ws,
                    const Workspace &w, hipStream_t stream);
+int launch_phi_psi(const void *q, Strides3 qs, const void *k, Strides3 ks, const void *v, Strides3 vs,
+                   const Shape &s, char *ws, const Workspace &w, float *mu_q_out, float *mu_k_out,
+                   hipStream_t stream);
 int launch_export_vq(const Shape &s, const char *ws, const Workspace &w, int8_t *vq, float *delta,
                      hipStream_t stream);
 int launch_logits_popcount(const uint32_t *q_bits, const uint32_t *k_bits, const Shape &s,

@@ -148,11 +148,21 @@ __global__ __launch_bounds__(PREP_THREADS) void v_absmax_kernel(const uint16_t *
 
 // Longer sequences, step 2: one key block of one head (V codes and, if k_bits is
 // not null, the key operand).
+// Optional last step of Eq. 5's abs-means in v_quant_kernel: the per-chunk partial sums of |q|
+// and |k| written by phi_psi1_kernel are added in a FIXED order (each lane its chunks in
+// ascending order, then a fixed shuffle tree), so the means are the same bits on every run.
+struct MuReduce {
+    const float *psum;          // [BH][nchunk][2], or null: nothing to do
+    float *mu_q, *mu_k;         // [BH]
+    float *mu_q_out, *mu_k_out; // optional copies for the caller
+    float inv_count;
+};
+
 template <int C16>
 __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(
     const uint16_t *__restrict__ v, Strides3 vs, const uint32_t *__restrict__ k_bits, int H, int N,
     int d, int DKP, int nchunk, int nblk, const float *__restrict__ amax, float *__restrict__ delta,
-    int img_bytes, int KP, int v_off, int cs_off, char *__restrict__ img) {
+    int img_bytes, int KP, int v_off, int cs_off, char *__restrict__ img, MuReduce mr) {
     __shared__ __attribute__((aligned(16))) float sdelta[8 * C16], srlo[8 * C16], srhi[8 * C16];
     __shared__ __attribute__((aligned(16))) int8_t tile[128 * (BV + 16)];
     const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
@@ -162,6 +172,26 @@ __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(
     if (k_bits != nullptr) {
         const int W = (d + 31) / 32;
         expand_k_block(k_bits + (int64_t)bh * N * W, N, d, W, blk, KP, dst);
+    }
+    if (mr.psum != nullptr && blk == 0 && threadIdx.x < 64) {
+        const float *ps = mr.psum + (int64_t)bh * nchunk * 2;
+        float sq = 0.0f, sk = 0.0f;
+        for (int j = threadIdx.x; j < nchunk; j += 64) {
+            sq += ps[2 * j];
+            sk += ps[2 * j + 1];
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            sq += __shfl_down(sq, off, 64);
+            sk += __shfl_down(sk, off, 64);
+        }
+        if (threadIdx.x == 0) {
+            const float mq = sq * mr.inv_count, mk = sk * mr.inv_count;
+            mr.mu_q[bh] = mq;
+            mr.mu_k[bh] = mk;
+            if (mr.mu_q_out) mr.mu_q_out[bh] = mq;
+            if (mr.mu_k_out) mr.mu_k_out[bh] = mk;
+        }
     }
     // The head's absmax from the per-chunk partials: all threads load (independent,
     // coalesced), the maximum is taken in LDS on the bit patterns (non-negative floats
@@ -194,6 +224,121 @@ __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(
         if (blk == 0) delta[(int64_t)bh * DKP + threadIdx.x] = dl;
     }
     quant_v_block<C16>(vb, vs.n, N, DKP, blk, sdelta, srlo, srhi, tile, v_off, cs_off, dst);
+}
+
+// Inverse of key_of_position: where key offset o (0 <= o < BV) sits in a block image.
+__device__ __forceinline__ int position_of_key(int o) {
+    const int g = o >> 6, t = (o >> 4) & 3, r = o & 15;
+    return 32 * t + 8 * (r >> 2) + 4 * g + (r & 3);
+}
+
+// phi of Alg. 1 (Eq. 5) for Q and K and the first half of psi (Eq. 7) in ONE pass over the bf16
+// inputs, for the entry point that takes Q, K and V themselves: a workgroup owns VCHUNK = 256
+// tokens of one head and
+//   * packs the sign words of its queries (assembled per token in LDS, stored as whole words),
+//   * turns the signs of its keys straight into the FP4 rows of the block images (the key
+//     sign words never exist in memory),
+//   * reduces the per-channel absmax of its V rows (the partials the quantisation launch
+//     combines), and
+//   * leaves its partial sums of |q| and |k| for the fixed-order reduction of the abs-means.
+// A thread owns one 8-channel chunk of every RT-th token, so consecutive lanes read whole
+// rows; all of a thread's loads go out before the first is used.
+struct PhiPsi1Args {
+    const uint16_t *q, *k, *v;
+    Strides3 qs, ks, vs;
+    uint32_t *q_bits;   // [BH][N][W]
+    char *img;          // block images
+    float *amax;        // [BH][nchunk][DKP]
+    float *psum;        // [BH][nchunk][2]
+    int H, N, d, DKP, nchunk, nblk, img_bytes, KP;
+};
+
+template <int C16>
+__global__ __launch_bounds__(PREP_THREADS) void phi_psi1_kernel(const PhiPsi1Args a) {
+    constexpr int W = (C16 + 3) / 4;
+    constexpr int RT = PREP_THREADS / C16;            // tokens per pass
+    constexpr int NP = (VCHUNK + RT - 1) / RT;        // passes
+    constexpr int D = 8 * C16;
+    __shared__ uint32_t words[VCHUNK * W];
+    __shared__ float smax[RT * D];
+    __shared__ float wsum[2][PREP_THREADS / 64];
+    const int chunk = blockIdx.x % a.nchunk, bh = blockIdx.x / a.nchunk;
+    const int b = bh / a.H, h = bh % a.H;
+    const int N = a.N, n0 = chunk * VCHUNK, n1 = min(N, n0 + VCHUNK);
+    const uint16_t *qb = a.q + (int64_t)b * a.qs.b + (int64_t)h * a.qs.h;
+    const uint16_t *kb = a.k + (int64_t)b * a.ks.b + (int64_t)h * a.ks.h;
+    const uint16_t *vb = a.v + (int64_t)b * a.vs.b + (int64_t)h * a.vs.h;
+    const int c = threadIdx.x % C16, r0 = threadIdx.x / C16;
+    const bool on = r0 < RT;
+
+    // (unconditional loads from clamped rows, masked where they are used)
+    u4 xq[NP], xk[NP], xv[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int tok = min(n0 + r0 + p * RT, N - 1);
+        xq[p] = *reinterpret_cast<const u4 *>(qb + (int64_t)tok * a.qs.n + 8 * c);
+        xk[p] = *reinterpret_cast<const u4 *>(kb + (int64_t)tok * a.ks.n + 8 * c);
+        xv[p] = *reinterpret_cast<const u4 *>(vb + (int64_t)tok * a.vs.n + 8 * c);
+    }
+    for (int i = threadIdx.x; i < VCHUNK * W; i += PREP_THREADS) words[i] = 0u;
+    // image words no key of the sequence fills: channels beyond d, positions beyond N
+    {
+        const int KW = a.KP / 4;  // 4-byte words (8 channels each) per image row
+        for (int i = threadIdx.x; i < VCHUNK * KW; i += PREP_THREADS) {
+            const int slot = i / KW, w4 = i % KW;           // slot: block-local position
+            const int blk = 2 * chunk + slot / BV, pos = slot % BV;
+            const int key = blk * BV + key_of_position(pos);
+            if (blk < a.nblk && (key >= N || w4 >= C16))
+                *reinterpret_cast<unsigned *>(a.img + ((int64_t)bh * a.nblk + blk) * a.img_bytes + (int64_t)pos * a.KP +
+                                              16 * k_chunk(pos, w4 >> 2, a.KP) + 4 * (w4 & 3)) = 0u;
+        }
+    }
+    __syncthreads();
+
+    float qsum = 0.0f, ksum = 0.0f;
+    unsigned mb[4] = {0u, 0u, 0u, 0u};
+    uint8_t *bytes = reinterpret_cast<uint8_t *>(words);
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int tok = n0 + r0 + p * RT;
+        if (on && r0 + p * RT < VCHUNK && tok < n1) {
+            bytes[(tok - n0) * (4 * W) + c] = (uint8_t)sign_bits8_abs(xq[p], qsum);
+            const unsigned kbits = sign_bits8_abs(xk[p], ksum);
+            const int blk = tok / BV, pos = position_of_key(tok % BV);
+            *reinterpret_cast<unsigned *>(a.img + ((int64_t)bh * a.nblk + blk) * a.img_bytes + (int64_t)pos * a.KP +
+                                          16 * k_chunk(pos, c >> 2, a.KP) + 4 * (c & 3)) = fp4_pm1_from_bits8(kbits);
+            absmax_acc(mb, xv[p]);
+        }
+    }
+    if (on) {
+        float m[8];
+        absmax_floats(mb, m);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) smax[r0 * D + 8 * c + i] = m[i];
+    }
+    // the two partial sums of the workgroup, in a fixed order
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        qsum += __shfl_down(qsum, off, 64);
+        ksum += __shfl_down(ksum, off, 64);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        wsum[0][threadIdx.x >> 6] = qsum;
+        wsum[1][threadIdx.x >> 6] = ksum;
+    }
+    __syncthreads();
+    if (threadIdx.x < D) {
+        float m = 0.0f;
+        for (int r = 0; r < RT; ++r) m = fmaxf(m, smax[r * D + threadIdx.x]);
+        a.amax[((int64_t)bh * a.nchunk + chunk) * a.DKP + threadIdx.x] = m;
+    }
+    if (threadIdx.x < 2) {
+        float t = 0.0f;
+        for (int i = 0; i < PREP_THREADS / 64; ++i) t += wsum[threadIdx.x][i];
+        a.psum[((int64_t)bh * a.nchunk + chunk) * 2 + threadIdx.x] = t;
+    }
+    uint32_t *ob = a.q_bits + ((int64_t)bh * N + n0) * W;
+    for (int i = threadIdx.x; i < (n1 - n0) * W; i += PREP_THREADS) ob[i] = words[i];
 }
 
 // Short sequences (at most two key blocks): everything for one head in ONE launch and ONE
@@ -348,7 +493,45 @@ static void launch_quant_v_t(const void *v, Strides3 vs, const uint32_t *k_bits,
                        0, stream, vp, vs, s.H, s.N, s.DKP, s.nchunk, amax);
     hipLaunchKernelGGL(v_quant_kernel<C16>, dim3((unsigned)s.nblk * s.BH), dim3(PREP_THREADS), 0,
                        stream, vp, vs, k_bits, s.H, s.N, s.d, s.DKP, s.nchunk, s.nblk, amax, delta,
-                       w.img_bytes, KP, v_off, cs_off, ws + w.img);
+                       w.img_bytes, KP, v_off, cs_off, ws + w.img, MuReduce{nullptr, nullptr, nullptr, nullptr, nullptr, 0.0f});
+}
+
+// phi + psi for the entry point that takes Q, K, V: two launches (see phi_psi1_kernel).
+template <int C16>
+static void launch_phi_psi_t(const void *q, Strides3 qs, const void *k, Strides3 ks, const void *v, Strides3 vs,
+                             const Shape &s, char *ws, const Workspace &w, float *mu_q_out, float *mu_k_out,
+                             hipStream_t stream) {
+    int KP, v_off, cs_off;
+    image_offsets(s.DK, &KP, &v_off, &cs_off);
+    float *amax = reinterpret_cast<float *>(ws + w.amax);
+    float *delta = reinterpret_cast<float *>(ws + w.delta);
+    float *psum = reinterpret_cast<float *>(ws + w.psum);
+    float *mu = reinterpret_cast<float *>(ws + w.mu);
+    PhiPsi1Args a;
+    a.q = static_cast<const uint16_t *>(q); a.k = static_cast<const uint16_t *>(k); a.v = static_cast<const uint16_t *>(v);
+    a.qs = qs; a.ks = ks; a.vs = vs;
+    a.q_bits = reinterpret_cast<uint32_t *>(ws + w.qbits);
+    a.img = ws + w.img; a.amax = amax; a.psum = psum;
+    a.H = s.H; a.N = s.N; a.d = s.d; a.DKP = s.DKP; a.nchunk = s.nchunk; a.nblk = s.nblk;
+    a.img_bytes = w.img_bytes; a.KP = KP;
+    hipLaunchKernelGGL(phi_psi1_kernel<C16>, dim3((unsigned)s.nchunk * s.BH), dim3(PREP_THREADS), 0, stream, a);
+    const MuReduce mr = {psum, mu, mu + s.BH, mu_q_out, mu_k_out, (float)(1.0 / ((double)s.N * (double)s.d))};
+    hipLaunchKernelGGL(v_quant_kernel<C16>, dim3((unsigned)s.nblk * s.BH), dim3(PREP_THREADS), 0, stream,
+                       a.v, vs, static_cast<const uint32_t *>(nullptr), s.H, s.N, s.d, s.DKP, s.nchunk, s.nblk,
+                       amax, delta, w.img_bytes, KP, v_off, cs_off, ws + w.img, mr);
+}
+
+int launch_phi_psi(const void *q, Strides3 qs, const void *k, Strides3 ks, const void *v, Strides3 vs,
+                   const Shape &s, char *ws, const Workspace &w, float *mu_q_out, float *mu_k_out,
+                   hipStream_t stream) {
+    switch (s.d / 8) {
+#define CASE(c) case c: launch_phi_psi_t<c>(q, qs, k, ks, v, vs, s, ws, w, mu_q_out, mu_k_out, stream); break;
+        CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8)
+        CASE(9) CASE(10) CASE(11) CASE(12) CASE(13) CASE(14) CASE(15) CASE(16)
+#undef CASE
+        default: return BINATTN_ERR_SHAPE;
+    }
+    return check_launch();
 }
 
 // V quantisation and (if k_bits is not null) the key operand into the block images.

@@ -741,6 +741,51 @@ def test_forward_fused_more_heads_than_cus(layout):
     assert np.abs(got - run_forward(x, x.bias)).max() <= 2e-3
 
 
+# ---- the one-call entry point from the bf16 tensors -------------------------------------------
+@pytest.mark.parametrize("B,H,N,d", [(2, 2, 197, 64), (1, 2, 257, 72), (2, 1, 384, 64), (1, 3, 520, 128), (4, 1, 1160, 32),
+                                     (1, 2, 1024, 72), (3, 1, 1160, 104), (1, 1, 2304, 8), (2, 2, 700, 96)])
+def test_attention_one_call_matches_oracle(B, H, N, d):
+    say(f"binattn_attention B={B} H={H} N={N} d={d}")
+    x = small_inputs(B, H, N, d, 240 + N, extra="k_channel_offset")
+    mq = torch.zeros(B, H, dtype=torch.float32, device="cuda")
+    mk = torch.zeros_like(mq)
+    out = ba.attention(dev(x.q), dev(x.k), dev(x.v), dev(x.bias), x.scale, mu_q=mq, mu_k=mk)
+    torch.cuda.synchronize()
+    got = gpu_out_f64(out)
+    for b in range(B):
+        for h in range(H):
+            assert float(mq[b, h]) == pytest.approx(orc.abs_mean(np_bits(x.q[b, h])), rel=2e-6)
+            assert float(mk[b, h]) == pytest.approx(orc.abs_mean(np_bits(x.k[b, h])), rel=2e-6)
+    check_close(got, oracle_forward(x, x.bias)["O2"], "out vs O2")
+    alg = oracle_algorithm1(x, x.bias, Bv=128)
+    err = np.abs(got - alg)
+    say(f"    vs Alg.1(Bv=128): max abs err {err.max():.3e}")
+    assert np.all(err <= 2e-3 + 2 ** -7 * np.abs(alg))
+    # the three-call path computes the same thing (its abs-means may differ in the last bits)
+    assert np.abs(got - run_forward(x, x.bias)).max() <= 2e-3
+
+
+def test_attention_one_call_strided_inputs_no_bias_and_repeatability():
+    # [B, N, H, d] storage seen as [B, H, N, d]; no bias; and the same bits on every run (the
+    # abs-means are reduced in a fixed order, no atomics anywhere on this path)
+    B, H, N, d = 2, 3, 2600, 72
+    x = small_inputs(B, H, N, d, 5151)
+    q, k, v = (dev(t).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (x.q, x.k, x.v))
+    ws = ba.alloc_workspace(B, H, N, d, "cuda")
+    outs, mus = [], []
+    for i in range(3):
+        mq = torch.zeros(B, H, dtype=torch.float32, device="cuda")
+        ws.fill_(0xAB if i == 1 else 0)             # stale workspace contents must not matter
+        outs.append(ba.attention(q, k, v, None, x.scale, workspace=ws, mu_q=mq).clone())
+        mus.append(mq)
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    assert torch.equal(mus[0], mus[1]) and torch.equal(mus[0], mus[2])
+    rows = np.arange(0, N, 41)
+    ref = oracle_forward(x, None, rows=rows)["O2"]
+    check_close(gpu_out_f64(outs[0])[:, :, rows], ref, "one call, strided, no bias vs O2")
+
+
 # ---- the five workloads, at full size, in the launch configuration bench.py times --------
 def _workload_check(name, heads=None, rows=None, rows_per_head=None, with_bias=True, flags=0):
     """Run pack_qk + forward on workload `name` and compare with the oracle, head by head.
