@@ -158,8 +158,9 @@ int binattn_attend_axial(const uint32_t *q_bits, const float *mu_q, const float 
  * row-major order, n = iy * Gx + ix, with Gy * Gx = N, and
  *     b_ij = table[h][iy - jy + Gy - 1][ix - jx + Gx - 1].
  *   table : float32 [H, 2 Gy - 1, 2 Gx - 1] contiguous, shared over the batch, finite values.
- *   Gx    : 16 or 32;  Gy in [1, 32]  (BINATTN_ERR_SHAPE otherwise: the head's table is
- *           held in LDS; larger grids take the dense or the decomposed form).
+ *   Gx    : a power of two in [16, 256];  Gy in [1, 256]  (BINATTN_ERR_SHAPE otherwise).
+ *           Up to 32 x 32 the head's whole table is held in LDS; larger grids stage, per key
+ *           block, only the table rows that block touches.
  * Everything else as binattn_attend; BINATTN_FLAG_NO_BIAS ignores the table.
  */
 int binattn_attend_relpos(const uint32_t *q_bits, const float *mu_q, const float *mu_k,
@@ -250,7 +251,7 @@ int binattn_attention(const void *q, const void *k, const void *v, const int64_t
 
 /*
  * binattn_forward_fused with the relative-position table of binattn_attend_relpos as bias
- * (table, Gy, Gx as there; Gy * Gx = N <= 256): for a 16 x 16 token grid the whole layer is
+ * (table, Gy, Gx as there, with Gx <= 32 and Gy <= 32; Gy * Gx = N <= 256): for a 16 x 16 token grid the whole layer is
  * one launch and no [N, N] bias exists anywhere.
  */
 int binattn_forward_fused_relpos(const void *q, const void *k, const void *v, const int64_t q_strides[3],

@@ -152,11 +152,12 @@ struct RawInputs {
 
 // BIAS_AXIAL arguments: tables present and aligned, Gx a power of two in [16, 256],
 // Gy in [1, 256], Gy * Gx = N.
-// BIAS_TABLE: table present and aligned, Gx a power of two in [16, 32], Gy in [1, 32].
-int check_axial(const AxialBias &ax, int N) {
+// Full table: present and aligned, same grid limits; the single-launch form (small = true)
+// holds the whole table in LDS and stops at 32 x 32.
+int check_axial(const AxialBias &ax, int N, bool small = false) {
     const bool full = ax.table != nullptr;
     if (!full && (!ax.y || !ax.x)) return BINATTN_ERR_NULL;
-    const int gmax = full ? TABLE_MAX_G : AXIAL_MAX_G;
+    const int gmax = small ? TABLE_MAX_G : AXIAL_MAX_G;
     if (ax.Gy < 1 || ax.Gy > gmax || ax.Gx < 16 || ax.Gx > gmax ||
         (ax.Gx & (ax.Gx - 1)) != 0 || (int64_t)ax.Gy * ax.Gx != N)
         return BINATTN_ERR_SHAPE;
@@ -188,9 +189,10 @@ int attend_impl(const uint32_t *q_bits, const float *mu_q, const float *mu_k, co
     int gx_shift = 0;
     bool wide_rows2 = false;
     if (ax != nullptr) {
-        if ((rc = check_axial(*ax, N)) != BINATTN_OK) return rc;
+        if ((rc = check_axial(*ax, N, raw != nullptr && ax->table != nullptr)) != BINATTN_OK) return rc;
         while ((1 << gx_shift) < ax->Gx) ++gx_shift;
-        if (!no_bias) mode = ax->table ? BIAS_TABLE : BIAS_AXIAL;
+        const bool small_grid = ax->Gx <= TABLE_MAX_G && ax->Gy <= TABLE_MAX_G;
+        if (!no_bias) mode = !ax->table ? BIAS_AXIAL : small_grid ? BIAS_TABLE : BIAS_TABLE_BLK;
     } else if (use_bias) {
         if (bias_dtype != BINATTN_BIAS_BF16 && bias_dtype != BINATTN_BIAS_F32) return BINATTN_ERR_DTYPE;
         if (!bias_strides) return BINATTN_ERR_NULL;

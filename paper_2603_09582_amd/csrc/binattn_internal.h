@@ -156,12 +156,14 @@ enum BiasMode {
     BIAS_BF16_LDS = 5,  // rows 16-byte aligned, N % 8 == 0: tile staged global -> LDS asynchronously
     BIAS_AXIAL = 7,     // b_ij = y[iy - jy] + x[ix - jx] on a Gy x Gx token grid, tables held in LDS
     BIAS_TABLE = 9,     // b_ij = t[iy - jy][ix - jx]: the full relative-position table of the head in LDS
+    BIAS_TABLE_BLK = 13, // the same table for larger grids: only the rows a key block needs, staged per block
     BIAS_LUT = 11       // no bias: 255 exp(S - m) read from a per-head table indexed by (m - I) / 2
 };
 
 // largest grid side of BIAS_AXIAL (the tables of one head live in LDS)
 constexpr int AXIAL_MAX_G = 256;
-// largest grid side of BIAS_TABLE ((2 G - 1)^2 entries per head)
+// largest grid side of BIAS_TABLE ((2 G - 1)^2 entries per head held in LDS); larger grids
+// (up to AXIAL_MAX_G) take BIAS_TABLE_BLK
 constexpr int TABLE_MAX_G = 32;
 
 struct FusedParams {

@@ -128,6 +128,18 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     constexpr bool TABLE = MODE == BIAS_TABLE;
     constexpr int TBP = 2 * TABLE_MAX_G + 16;
     __shared__ float tab2[TABLE ? (2 * TABLE_MAX_G - 1) * TBP : 4];
+    // BIAS_TABLE_BLK: the same bias for grids whose table does not fit LDS.  A 128-key block
+    // covers 128 / Gx grid rows (or part of one) and so do the item's 128 queries, so a block
+    // needs only the table rows iy - jy in [iy_lo - jy_hi, iy_hi - jy_lo]: at most 15 rows of
+    // 2 Gx - 1 entries.  They are staged per block, divided by alpha and reversed in x, at a
+    // pitch of 4 Gx entries (a power of two, at most 1024 entries in all), double-buffered: the
+    // entries for the next block of the stream are loaded at the start of a block and written
+    // to the other buffer at its end.  Lane windows are read as in BIAS_TABLE.
+    constexpr bool TBLK = MODE == BIAS_TABLE_BLK;
+    constexpr int TBLK_N = 1024;
+    constexpr int TBLK_PER = TBLK_N / FUSED_THREADS;   // entries a thread stages (NB = 1 only)
+    static_assert(!TBLK || (NB == 1 && WIDE == WIDE_NONE), "per-block table rows: 4-wave workgroups");
+    __shared__ float tblk[TBLK ? 2 * TBLK_N : 4];
     // BIAS_LUT (no bias): the logit takes only the d + 1 values alpha * I, I = d, d - 2, ..., -d, and
     // the running maximum is one of them, so 255 * exp(S - m) is one of d + 1 numbers that depend
     // on the head alone: lut[k] = 255 * exp(-2 alpha k) for m - I = 2 k.  Entries d + 1 ... 2 d + 1
@@ -343,6 +355,11 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
             ax_wb = (qc >> p.gx_shift) + p.Gy - 1;      // table row of key row 0
             __syncthreads();
         }
+        if (TBLK) {
+            const int qc = min(q, N - 1);
+            ax_ub = p.Gx - 1 - (qc & (p.Gx - 1));                               // reversed-row index of key column 0
+            ax_wb = (qc >> p.gx_shift) - ((t.rb * BR) >> p.gx_shift);           // grid row inside the item's range
+        }
         m_run = -INFINITY;
         l_run = 0.0f;
         rho = 0.0f;
@@ -453,6 +470,39 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
             }
     };
 
+    // ---- BIAS_TABLE_BLK: the table rows of one (item, key block) ------------------------
+    // first row difference iy - jy of the block, and how many
+    auto tblk_range = [&](const Item &t, int blk, int *dy_min) -> int {
+        const int iy_lo = (t.rb * BR) >> p.gx_shift, iy_hi = min((t.rb * BR + BR - 1) >> p.gx_shift, p.Gy - 1);
+        const int jy_lo = (blk * BV) >> p.gx_shift, jy_hi = min((blk * BV + BV - 1) >> p.gx_shift, p.Gy - 1);
+        *dy_min = iy_lo - jy_hi;
+        return iy_hi - jy_lo - *dy_min + 1;
+    };
+    float tstage[TBLK ? TBLK_PER : 1];
+    auto tblk_load = [&](const Item &t, int blk) {  // global loads only
+        int dy_min;
+        const int nrows = tblk_range(t, blk, &dy_min);
+        const int LX = 2 * p.Gx - 1, LY = 2 * p.Gy - 1, sh = p.gx_shift + 2;
+        const float *tb = p.table + (int64_t)t.h * LY * LX;
+#pragma unroll
+        for (int j = 0; j < TBLK_PER; ++j) {
+            const int i = threadIdx.x + j * FUSED_THREADS;
+            const int row = i >> sh, kk = i & ((4 << p.gx_shift) - 1);
+            const bool on = row < nrows && kk < LX;
+            const float x = tb[on ? (int64_t)(dy_min + row + p.Gy - 1) * LX + (LX - 1 - kk) : 0];
+            tstage[j] = on ? x : 0.0f;
+        }
+    };
+    auto tblk_store = [&](float *dst, float ia) {
+#pragma unroll
+        for (int j = 0; j < TBLK_PER; ++j) dst[threadIdx.x + j * FUSED_THREADS] = tstage[j] * ia;
+    };
+    // 1 / |alpha| of an item from the abs-means fetched for it (as begin_item computes it)
+    auto inv_alpha_of = [&](float muq, float muk) {
+        const float alpha = p.scale * muq * muk;
+        return fabsf(alpha) < 1e-30f ? 1.0f : 1.0f / fabsf(alpha);
+    };
+
     // ---- stream position --------------------------------------------------------
     int it = 0;        // key block inside the current item
     const bool younger = 2 * blockIdx.x >= gridDim.x;
@@ -462,7 +512,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     // One key/value block of the stream: compute block `it` of item `cur` from the image at
     // `ibuf` (and bias tile at `bbuf`), prefetch the next block of the stream into the LDS
     // offsets `inxt` / `bnxt`.  Returns false after the last block of the last item.
-    auto step = [&](const char *ibuf, unsigned inxt, const char *bbuf, unsigned bnxt) -> bool {
+    auto step = [&](const char *ibuf, unsigned inxt, const char *bbuf, unsigned bnxt, int tpar) -> bool {
         const bool last = it + 1 == p.nblk;          // last block of this item
         const bool more = !last || (PERSIST && nxt.valid);  // the stream goes on
         // 0. start the copies for the next block of the stream
@@ -475,6 +525,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         if (!ONEHEAD && it == 0 && (ROWS2 ? wreg : wave) == 0 && lane < DKP / 4)  // delta_v of this item, for its epilogue
             dma16(p.delta + (int64_t)cur.bh * DKP, 16 * lane, lds_offset(&sdelta[parity][isel][0]));
         if (sw && nxt.valid) fetch_item_regs(nxt);
+        if (TBLK && more) tblk_load(sw ? nxt : cur, nblkidx);  // lands during this block, stored at its end
 
         // Two 4-wave workgroups share a CU, and the SIMDs issue the older wave first: the
         // workgroup dispatched first then runs ~25 % faster than the other and leaves the CU
@@ -519,6 +570,20 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
                 const int key0 = it * BV + 64 * g + 16 * t;  // 16 keys of one grid row (Gx >= 16)
                 const int jx0 = key0 & (p.Gx - 1), jy = min(key0 >> p.gx_shift, p.Gy - 1);
                 const float *win = tab2 + (ax_wb - jy) * TBP + ax_ub + jx0;
+                v16f cin;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) cin[r] = win[r];
+                wt[t] = 0.0f;
+                T[t] = qk_mfma<DK2>(ka[t], qB, cin);
+            }
+        } else if (TBLK) {
+            const float *tcur = tblk + tpar * TBLK_N;
+            const int jy_hi = min((it * BV + BV - 1) >> p.gx_shift, p.Gy - 1);
+#pragma unroll
+            for (int t = 0; t < KT; ++t) {
+                const int key0 = it * BV + 64 * g + 16 * t;  // 16 keys of one grid row (Gx >= 16)
+                const int jx0 = key0 & (p.Gx - 1), jy = min(key0 >> p.gx_shift, p.Gy - 1);
+                const float *win = tcur + ((ax_wb + jy_hi - jy) << (p.gx_shift + 2)) + ax_ub + jx0;
                 v16f cin;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) cin[r] = win[r];
@@ -696,6 +761,8 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
             rho = 0.0f;
         }
 
+        if (TBLK && more)
+            tblk_store(tblk + (tpar ^ 1) * TBLK_N, sw ? inv_alpha_of(pend_muq, pend_muk) : inv_alpha);
         __builtin_amdgcn_sched_barrier(0);  // keep the wait at the very end of the block
         wait_vmem();      // this wave's copies for the next block have landed
         __syncthreads();  // everyone is done with this block's buffers, the next ones are complete
@@ -887,13 +954,17 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         if (MODE == BIAS_BF16_VEC) load_bias_vec(brow, 0);
         if (LDS_BIAS) dma_bias(bsrc, 0, lds_offset(bA));
     }
+    if (TBLK) {
+        tblk_load(cur, 0);
+        tblk_store(tblk, inv_alpha);
+    }
     wait_vmem();
     __syncthreads();
 
     const char *imgA = bufA + isel * L::BYTES, *imgB = bufB + isel * L::BYTES;
     for (;;) {
-        if (!step(imgA, lds_offset(bufB), bA, lds_offset(bB))) break;
-        if (!step(imgB, lds_offset(bufA), bB, lds_offset(bA))) break;
+        if (!step(imgA, lds_offset(bufB), bA, lds_offset(bB), 0)) break;
+        if (!step(imgB, lds_offset(bufA), bB, lds_offset(bA), 1)) break;
     }
 }
 
@@ -925,6 +996,7 @@ int launch_fused_dk(const FusedParams &p, int mode, hipStream_t stream) {
     switch (mode) {
 #define CASE(M) case M: hipLaunchKernelGGL((fused_kernel<DK, M, 1>), grid, block, 0, stream, p); break;
         CASE(BIAS_NONE) CASE(BIAS_LUT) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC) CASE(BIAS_AXIAL) CASE(BIAS_TABLE)
+        CASE(BIAS_TABLE_BLK)
 #undef CASE
         case BIAS_BF16_LDS:
             if constexpr (DK <= 3) {

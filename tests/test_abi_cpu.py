@@ -124,8 +124,8 @@ def test_forward_relpos_rejects_bad_arguments():
     assert fwd_relpos(table=None) == -1 and fwd_relpos(qb=None) == -1 and fwd_relpos(v=None) == -1
     assert fwd_relpos(Gx=24, Gy=16, N=384) == -2     # Gx not a power of two
     assert fwd_relpos(Gx=8, Gy=32) == -2             # Gx below 16
-    assert fwd_relpos(Gx=64, Gy=4) == -2             # Gx above 32
-    assert fwd_relpos(Gx=16, Gy=33, N=16 * 33) == -2 # Gy above 32
+    assert fwd_relpos(Gx=512, Gy=2, N=1024) == -2    # Gx above 256
+    assert fwd_relpos(Gx=16, Gy=257, N=16 * 257) == -2 # Gy above 256
     assert fwd_relpos(Gx=16, Gy=15) == -2            # Gy * Gx != N
     assert fwd_relpos(table=FAKE + 2) == -4
     assert fwd_relpos(wsb=100) == -5

@@ -519,7 +519,10 @@ def relpos_dense(table, Gy, Gx):
 
 
 @pytest.mark.parametrize("B,H,Gy,Gx,d", [(2, 2, 16, 16, 72), (1, 2, 32, 32, 72), (1, 2, 5, 32, 64),
-                                         (1, 1, 7, 16, 128), (2, 1, 1, 16, 8), (1, 3, 31, 32, 96)])
+                                         (1, 1, 7, 16, 128), (2, 1, 1, 16, 8), (1, 3, 31, 32, 96),
+                                         # beyond 32 x 32: table rows staged per key block
+                                         (1, 2, 33, 32, 64), (1, 1, 128, 16, 32), (2, 1, 48, 64, 72),
+                                         (1, 1, 19, 128, 128), (1, 2, 7, 256, 64), (1, 1, 64, 64, 104)])
 def test_relpos_table_matches_dense_oracle(B, H, Gy, Gx, d):
     N = Gy * Gx
     say(f"relative-position table B={B} H={H} grid {Gy}x{Gx} d={d}")
@@ -919,6 +922,40 @@ def test_axial_bias_at_the_128x128_grid_sampled_rows():
             assert np.all(err <= ATOL + RTOL * np.abs(o)), f"axial 128x128 head {(b, h)}: max abs err {err.max():.3e}"
             worst = max(worst, float(err.max()))
     say(f"    axial 128x128: max abs err {worst:.3e}")
+
+
+def test_relpos_table_at_the_128x128_grid_sampled_rows():
+    # the full relative-position table at the long-sequence workload's own grid (255 x 255 entries
+    # per head: 15 of them per key block in LDS)
+    w = wl.WORKLOADS["vit_hires"]
+    N, Gy, Gx = w.N, 128, 128
+    say("relative-position table on vit_hires (128 x 128 grid)")
+    x = wl.make_inputs(w, device="cuda", with_bias=False)
+    g = torch.Generator().manual_seed(4129)
+    table = torch.randn(w.H, 2 * Gy - 1, 2 * Gx - 1, generator=g) * 0.3
+    qb, kb, mq, mk = ba.pack_qk(x.q, x.k)
+    out = ba.forward_relpos(qb, kb, mq, mk, x.v, table.cuda(), x.scale)
+    torch.cuda.synchronize()
+    qh, kh, vh = (np_bits(t) for t in (x.q, x.k, x.v))
+    fixed = np.concatenate([np.arange(0, 40), np.arange(8170, 8210), np.arange(N - 40, N)])
+    n = np.arange(N)
+    jy, jx = n // Gx, n % Gx
+    full = np.zeros((N, N), dtype=np.float32)
+    worst = 0.0
+    for h in range(w.H):
+        for b in range(w.B):
+            r = np.unique(np.concatenate([fixed, np.random.default_rng(9 * h + b).integers(0, N, 40)]))
+            iy, ix = r // Gx, r % Gx
+            full[r] = table[h].numpy()[iy[:, None] - jy[None, :] + Gy - 1, ix[:, None] - jx[None, :] + Gx - 1]
+            q, k, v = qh[b, h], kh[b, h], vh[b, h]
+            vq, delta = orc.quant_v(v)
+            o = orc.attention_rows(q, k, v, full, x.scale, orc.abs_mean(q), orc.abs_mean(k), vq, delta,
+                                   rows=r, want=("O2",))["O2"]
+            got = gpu_out_f64(out[b, h][torch.as_tensor(r, device="cuda")])
+            err = np.abs(got - o)
+            assert np.all(err <= ATOL + RTOL * np.abs(o)), f"relpos 128x128 head {(b, h)}: max abs err {err.max():.3e}"
+            worst = max(worst, float(err.max()))
+    say(f"    relpos 128x128: max abs err {worst:.3e}")
 
 
 @pytest.mark.parametrize("B,H,N,d,kind", [(2, 1, 16384, 64, "one_hot"), (2, 1, 16384, 64, "few_visible"),
