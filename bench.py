@@ -339,16 +339,16 @@ def logits_rows(steps=20):
     return rows
 
 
-def probe_rows(iters=4096, blocks=256 * 16, reps=5):
+def probe_rows(iters=4096, blocks=256 * 16, reps=3):
     """Issue rate of the vector-ALU instruction kinds of the softmax (binattn_probe_valu): T
-    lane-instructions/s over the chip and the issue slots that implies against the 39.3 T/s of
-    256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz (at the clock the chip actually holds)."""
+    lane-instructions/s over the chip for each kind alone and mixed half and half with an FMA, a
+    byte conversion, an exponential and an OR (a mix that runs faster than either kind alone
+    shows that the two kinds issue side by side)."""
     import torch
     from paper_2603_09582_amd import binding as ba
     out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
-    rows = []
-    for label, op in ba.PROBE_OPS.items():
-        per_step = 2 if label == "cvt_pk_u8+or" else 1
+
+    def rate(op):
         ba.probe_valu(op, iters, blocks, out)
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
         for e in ev:
@@ -357,11 +357,15 @@ def probe_rows(iters=4096, blocks=256 * 16, reps=5):
             e[1].record()
         torch.cuda.synchronize()
         ms = statistics.median(a.elapsed_time(c) for a, c in ev)
-        rate = blocks * 256 * ba.PROBE_CHAINS * iters * per_step / (ms * 1e-3) / 1e12
-        rows.append({"op": label, "instructions_per_step": per_step, "ms": ms, "t_lane_instr_per_s": rate})
-    base = max(r["t_lane_instr_per_s"] for r in rows)
-    for r in rows:
-        r["issue_slots_vs_fastest"] = base / r["t_lane_instr_per_s"]
+        return blocks * 256 * ba.PROBE_CHAINS * iters / (ms * 1e-3) / 1e12
+
+    rows = []
+    for label, op in ba.PROBE_OPS.items():
+        row = {"op": label, "alone": rate(op | (op << 8))}
+        for partner in ba.PROBE_PARTNERS:
+            if partner != label:
+                row["with_" + partner] = rate(op | (ba.PROBE_OPS[partner] << 8))
+        rows.append(row)
     return rows
 
 
@@ -421,7 +425,11 @@ def profile_record(workload):
 
 
 def clock_state():
-    """Clocks and power as rocm-smi reports them (read-only), for the record."""
+    """Clocks and power as rocm-smi reports them (read-only), for the record.  Called before
+    anything touches the GPU (a process that has initialised the GPU must not start other
+    programs on this pool), and not at all under a profiler, which initialises the GPU first."""
+    if any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ) or "rocprof" in os.environ.get("LD_PRELOAD", ""):
+        return {"unavailable": "profiler run"}
     try:
         r = subprocess.run(["rocm-smi", "--showclocks", "--showpower", "--json"], capture_output=True,
                            text=True, timeout=20)
@@ -438,6 +446,7 @@ def main():
         print("bench.py measures one GPU: this build has no multi-GPU path (each (batch, head) problem "
               "is independent and would shard over them, or over query rows, with no exchange step). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    clocks = clock_state()
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     from paper_2603_09582_amd import workloads as wl
@@ -473,7 +482,7 @@ def main():
             "t_bound_ms": bd["t_bound_fused_ms"], "frac_of_t_bound": bd["t_bound_fused_ms"] / res["fused_ms"],
             "mfma_int8_frac": res["mfma_tops_algorithmic"] / MFMA_I8_PEAK_TOPS,
             "hbm_frac": res["fused_hbm_gbs"] / HBM_PEAK_GBS, "hbm_gbs": res["fused_hbm_gbs"]},
-        "clocks": clock_state(),
+        "clocks": clocks,
     }
     del x
     torch.cuda.empty_cache()

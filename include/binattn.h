@@ -285,16 +285,23 @@ int binattn_quant_v_debug(const void *v, const int64_t v_strides[3], int B, int 
 
 /*
  * Measurement aid, not part of the attention path: runs `blocks` workgroups of 256 lanes,
- * each lane issuing 8 * iters instructions of ONE kind (BINATTN_PROBE_*) in eight independent
- * chains, and writes one float per lane to `out` (blocks * 256 floats).  Timing the launch
- * gives the chip's issue rate for that instruction: the roofline of the fused kernel counts
- * vector-ALU issue slots per (query, key) pair, and this is how the slots of v_exp_f32 (two)
- * and of the others (one) were measured.  BINATTN_PROBE_CVT_PK_U8 issues two instructions per
- * step (the conversion and an OR).  iters, blocks >= 1.
+ * each lane issuing 8 * iters vector-ALU instructions in eight independent chains, and writes
+ * one float per lane to `out` (blocks * 256 floats).  op = A | (B << 8) with A, B from
+ * BINATTN_PROBE_*: even chains issue kind A, odd chains kind B (B = A: one kind; B may
+ * otherwise be FMA, CVT_PK_U8, EXP2 or OR).  Timing the launch gives the chip's issue rate
+ * for that instruction or mix: the roofline of the fused kernel counts vector-ALU issue
+ * slots per (query, key) pair, and this is how the slots of v_exp_f32 (two) and of the others
+ * (one) were measured, and which kinds issue side by side.  iters, blocks >= 1.
  */
 enum {
     BINATTN_PROBE_FMA = 0, BINATTN_PROBE_EXP2 = 1, BINATTN_PROBE_ADD = 2, BINATTN_PROBE_MAX3 = 3,
-    BINATTN_PROBE_CVT_PK_U8 = 4, BINATTN_PROBE_CVT_F32_I32 = 5
+    BINATTN_PROBE_CVT_PK_U8 = 4, BINATTN_PROBE_CVT_F32_I32 = 5, BINATTN_PROBE_OR = 6, BINATTN_PROBE_MUL = 7,
+    BINATTN_PROBE_LSHL = 8, BINATTN_PROBE_AND = 9, BINATTN_PROBE_XOR = 10, BINATTN_PROBE_MIN3_I32 = 11,
+    BINATTN_PROBE_LSHL_ADD = 12, BINATTN_PROBE_MOV = 13, BINATTN_PROBE_ADD_U32 = 14, BINATTN_PROBE_PERM = 15,
+    /* the softmax's own per-pair instruction mix on register data, 16 values per lane and step
+       (then iters counts steps); op = BINATTN_PROBE_SOFTMAX | (KiB of LDS per workgroup << 8)
+       pins the number of workgroups (of four waves) a compute unit can hold */
+    BINATTN_PROBE_SOFTMAX = 64
 };
 int binattn_probe_valu(int op, int iters, int blocks, float *out, void *stream);
 

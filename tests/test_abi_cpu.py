@@ -227,3 +227,4 @@ def test_probe_rejects_bad_arguments():
     assert L.binattn_probe_valu(0, 16, 4, None, None) == -1
     assert L.binattn_probe_valu(0, 0, 4, FAKE, None) == -2 and L.binattn_probe_valu(0, 16, 0, FAKE, None) == -2
     assert L.binattn_probe_valu(0, 16, 4, FAKE + 2, None) == -4
+    assert L.binattn_probe_valu(99, 16, 4, FAKE, None) == -8 and L.binattn_probe_valu(2 | (3 << 8), 16, 4, FAKE, None) == -8
