@@ -97,10 +97,11 @@ constexpr float PV_MAGIC_F = 12582912.0f;
 // Private workspace layout (all offsets 256-byte aligned).
 //   img   bytes [BH][nblk][Image<DK>::BYTES]
 //   delta f32   [BH][DKP]
-//   amax  f32   [BH][nchunk][DKP]           partial absmax of V
-// and, for the entry point that takes Q, K, V themselves:
+//   amax  f32   [BH][nblk][DKP]             partial absmax of V (per 256 tokens, or per key
+//                                           block on the path that takes Q, K, V themselves)
+// and, for that path:
 //   mu    f32   [2][BH]                     abs-means of Q and K
-//   psum  f32   [BH][nchunk][2]             their per-chunk partial sums
+//   psum  f32   [BH][nblk][2]               their partial sums per key block
 //   qbits u32   [BH][N][W]                  query sign words
 struct Workspace {
     size_t img, delta, amax, mu, psum, qbits, total;
@@ -115,9 +116,9 @@ inline Workspace make_workspace(const Shape &s) {
     size_t off = 0;
     w.img = off;   off = align256(off + (size_t)s.BH * s.nblk * w.img_bytes);
     w.delta = off; off = align256(off + (size_t)s.BH * s.DKP * 4);
-    w.amax = off;  off = align256(off + (size_t)s.BH * s.nchunk * s.DKP * 4);
+    w.amax = off;  off = align256(off + (size_t)s.BH * s.nblk * s.DKP * 4);
     w.mu = off;    off = align256(off + (size_t)2 * s.BH * 4);
-    w.psum = off;  off = align256(off + (size_t)s.BH * s.nchunk * 2 * 4);
+    w.psum = off;  off = align256(off + (size_t)s.BH * s.nblk * 2 * 4);
     w.qbits = off; off = align256(off + (size_t)s.BH * s.N * s.W * 4);
     w.total = off;
     return w;

@@ -162,18 +162,22 @@ template <int C16>
 __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(
     const uint16_t *__restrict__ v, Strides3 vs, const uint32_t *__restrict__ k_bits, int H, int N,
     int d, int DKP, int nchunk, int nblk, const float *__restrict__ amax, float *__restrict__ delta,
-    int img_bytes, int KP, int v_off, int cs_off, char *__restrict__ img, MuReduce mr) {
+    int img_bytes, int KP, int v_off, int cs_off, char *__restrict__ img, MuReduce mr, int bpw) {
+    // A workgroup takes bpw consecutive key blocks of one head (more than one for long
+    // sequences, where re-reading all absmax partials for every single block would cost more
+    // than the block itself).
     __shared__ __attribute__((aligned(16))) float sdelta[8 * C16], srlo[8 * C16], srhi[8 * C16];
     __shared__ __attribute__((aligned(16))) int8_t tile[128 * (BV + 16)];
-    const int blk = blockIdx.x % nblk, bh = blockIdx.x / nblk;
+    const int ngrp = (nblk + bpw - 1) / bpw;
+    const int blk0 = (blockIdx.x % ngrp) * bpw, bh = blockIdx.x / ngrp;
     const int b = bh / H, h = bh % H;
     const uint16_t *vb = v + (int64_t)b * vs.b + (int64_t)h * vs.h;
-    char *dst = img + ((int64_t)bh * nblk + blk) * img_bytes;
     if (k_bits != nullptr) {
         const int W = (d + 31) / 32;
-        expand_k_block(k_bits + (int64_t)bh * N * W, N, d, W, blk, KP, dst);
+        for (int blk = blk0; blk < min(nblk, blk0 + bpw); ++blk)
+            expand_k_block(k_bits + (int64_t)bh * N * W, N, d, W, blk, KP, img + ((int64_t)bh * nblk + blk) * img_bytes);
     }
-    if (mr.psum != nullptr && blk == 0 && threadIdx.x < 64) {
+    if (mr.psum != nullptr && blk0 == 0 && threadIdx.x < 64) {
         const float *ps = mr.psum + (int64_t)bh * nchunk * 2;
         float sq = 0.0f, sk = 0.0f;
         for (int j = threadIdx.x; j < nchunk; j += 64) {
@@ -221,9 +225,13 @@ __global__ __launch_bounds__(PREP_THREADS) void v_quant_kernel(
         float dl;
         quant_consts(__int_as_float(sabs[threadIdx.x]), &dl, &srlo[threadIdx.x], &srhi[threadIdx.x]);
         sdelta[threadIdx.x] = dl;
-        if (blk == 0) delta[(int64_t)bh * DKP + threadIdx.x] = dl;
+        if (blk0 == 0) delta[(int64_t)bh * DKP + threadIdx.x] = dl;
     }
-    quant_v_block<C16>(vb, vs.n, N, DKP, blk, sdelta, srlo, srhi, tile, v_off, cs_off, dst);
+    for (int blk = blk0; blk < min(nblk, blk0 + bpw); ++blk) {
+        quant_v_block<C16>(vb, vs.n, N, DKP, blk, sdelta, srlo, srhi, tile, v_off, cs_off,
+                           img + ((int64_t)bh * nblk + blk) * img_bytes);
+        __syncthreads();  // the tile is reused
+    }
 }
 
 // Inverse of key_of_position: where key offset o (0 <= o < BV) sits in a block image.
@@ -233,8 +241,9 @@ __device__ __forceinline__ int position_of_key(int o) {
 }
 
 // phi of Alg. 1 (Eq. 5) for Q and K and the first half of psi (Eq. 7) in ONE pass over the bf16
-// inputs, for the entry point that takes Q, K and V themselves: a workgroup owns VCHUNK = 256
-// tokens of one head and
+// inputs, for the entry point that takes Q, K and V themselves: a workgroup owns the BV = 128
+// tokens of one key block of one head (many small workgroups: the loads of one overlap the
+// arithmetic of its neighbours on the compute unit) and
 //   * packs the sign words of its queries (assembled per token in LDS, stored as whole words),
 //   * turns the signs of its keys straight into the FP4 rows of the block images (the key
 //     sign words never exist in memory),
@@ -248,23 +257,25 @@ struct PhiPsi1Args {
     Strides3 qs, ks, vs;
     uint32_t *q_bits;   // [BH][N][W]
     char *img;          // block images
-    float *amax;        // [BH][nchunk][DKP]
-    float *psum;        // [BH][nchunk][2]
-    int H, N, d, DKP, nchunk, nblk, img_bytes, KP;
+    float *amax;        // [BH][nblk][DKP]: one partial per key block
+    float *psum;        // [BH][nblk][2]
+    int H, N, d, DKP, nblk, img_bytes;
 };
 
 template <int C16>
 __global__ __launch_bounds__(PREP_THREADS) void phi_psi1_kernel(const PhiPsi1Args a) {
     constexpr int W = (C16 + 3) / 4;
     constexpr int RT = PREP_THREADS / C16;            // tokens per pass
-    constexpr int NP = (VCHUNK + RT - 1) / RT;        // passes
+    constexpr int NP = (BV + RT - 1) / RT;            // passes
     constexpr int D = 8 * C16;
-    __shared__ uint32_t words[VCHUNK * W];
+    constexpr int KW = 8 * ((W + 1) / 2);             // 4-byte words (8 channels each) per image row
+    __shared__ uint32_t words[BV * W];
     __shared__ float smax[RT * D];
     __shared__ float wsum[2][PREP_THREADS / 64];
-    const int chunk = blockIdx.x % a.nchunk, bh = blockIdx.x / a.nchunk;
+    const int chunk = blockIdx.x % a.nblk, bh = blockIdx.x / a.nblk;  // chunk = key block
     const int b = bh / a.H, h = bh % a.H;
-    const int N = a.N, n0 = chunk * VCHUNK, n1 = min(N, n0 + VCHUNK);
+    const int N = a.N, n0 = chunk * BV, n1 = min(N, n0 + BV);
+    char *image = a.img + ((int64_t)bh * a.nblk + chunk) * a.img_bytes;
     const uint16_t *qb = a.q + (int64_t)b * a.qs.b + (int64_t)h * a.qs.h;
     const uint16_t *kb = a.k + (int64_t)b * a.ks.b + (int64_t)h * a.ks.h;
     const uint16_t *vb = a.v + (int64_t)b * a.vs.b + (int64_t)h * a.vs.h;
@@ -280,18 +291,13 @@ __global__ __launch_bounds__(PREP_THREADS) void phi_psi1_kernel(const PhiPsi1Arg
         xk[p] = *reinterpret_cast<const u4 *>(kb + (int64_t)tok * a.ks.n + 8 * c);
         xv[p] = *reinterpret_cast<const u4 *>(vb + (int64_t)tok * a.vs.n + 8 * c);
     }
-    for (int i = threadIdx.x; i < VCHUNK * W; i += PREP_THREADS) words[i] = 0u;
+    for (int i = threadIdx.x; i < BV * W; i += PREP_THREADS) words[i] = 0u;
     // image words no key of the sequence fills: channels beyond d, positions beyond N
-    {
-        const int KW = a.KP / 4;  // 4-byte words (8 channels each) per image row
-        for (int i = threadIdx.x; i < VCHUNK * KW; i += PREP_THREADS) {
-            const int slot = i / KW, w4 = i % KW;           // slot: block-local position
-            const int blk = 2 * chunk + slot / BV, pos = slot % BV;
-            const int key = blk * BV + key_of_position(pos);
-            if (blk < a.nblk && (key >= N || w4 >= C16))
-                *reinterpret_cast<unsigned *>(a.img + ((int64_t)bh * a.nblk + blk) * a.img_bytes + (int64_t)pos * a.KP +
-                                              16 * k_chunk(pos, w4 >> 2, a.KP) + 4 * (w4 & 3)) = 0u;
-        }
+    for (int i = threadIdx.x; i < BV * KW; i += PREP_THREADS) {
+        const int pos = i / KW, w4 = i % KW;
+        const int key = n0 + key_of_position(pos);
+        if (key >= N || w4 >= C16)
+            *reinterpret_cast<unsigned *>(image + pos * (4 * KW) + 16 * k_chunk(pos, w4 >> 2, 4 * KW) + 4 * (w4 & 3)) = 0u;
     }
     __syncthreads();
 
@@ -301,12 +307,12 @@ __global__ __launch_bounds__(PREP_THREADS) void phi_psi1_kernel(const PhiPsi1Arg
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
         const int tok = n0 + r0 + p * RT;
-        if (on && r0 + p * RT < VCHUNK && tok < n1) {
+        if (on && r0 + p * RT < BV && tok < n1) {
             bytes[(tok - n0) * (4 * W) + c] = (uint8_t)sign_bits8_abs(xq[p], qsum);
             const unsigned kbits = sign_bits8_abs(xk[p], ksum);
-            const int blk = tok / BV, pos = position_of_key(tok % BV);
-            *reinterpret_cast<unsigned *>(a.img + ((int64_t)bh * a.nblk + blk) * a.img_bytes + (int64_t)pos * a.KP +
-                                          16 * k_chunk(pos, c >> 2, a.KP) + 4 * (c & 3)) = fp4_pm1_from_bits8(kbits);
+            const int pos = position_of_key(tok - n0);
+            *reinterpret_cast<unsigned *>(image + pos * (4 * KW) + 16 * k_chunk(pos, c >> 2, 4 * KW) + 4 * (c & 3)) =
+                fp4_pm1_from_bits8(kbits);
             absmax_acc(mb, xv[p]);
         }
     }
@@ -330,12 +336,12 @@ __global__ __launch_bounds__(PREP_THREADS) void phi_psi1_kernel(const PhiPsi1Arg
     if (threadIdx.x < D) {
         float m = 0.0f;
         for (int r = 0; r < RT; ++r) m = fmaxf(m, smax[r * D + threadIdx.x]);
-        a.amax[((int64_t)bh * a.nchunk + chunk) * a.DKP + threadIdx.x] = m;
+        a.amax[((int64_t)bh * a.nblk + chunk) * a.DKP + threadIdx.x] = m;
     }
     if (threadIdx.x < 2) {
         float t = 0.0f;
         for (int i = 0; i < PREP_THREADS / 64; ++i) t += wsum[threadIdx.x][i];
-        a.psum[((int64_t)bh * a.nchunk + chunk) * 2 + threadIdx.x] = t;
+        a.psum[((int64_t)bh * a.nblk + chunk) * 2 + threadIdx.x] = t;
     }
     uint32_t *ob = a.q_bits + ((int64_t)bh * N + n0) * W;
     for (int i = threadIdx.x; i < (n1 - n0) * W; i += PREP_THREADS) ob[i] = words[i];
@@ -493,7 +499,7 @@ static void launch_quant_v_t(const void *v, Strides3 vs, const uint32_t *k_bits,
                        0, stream, vp, vs, s.H, s.N, s.DKP, s.nchunk, amax);
     hipLaunchKernelGGL(v_quant_kernel<C16>, dim3((unsigned)s.nblk * s.BH), dim3(PREP_THREADS), 0,
                        stream, vp, vs, k_bits, s.H, s.N, s.d, s.DKP, s.nchunk, s.nblk, amax, delta,
-                       w.img_bytes, KP, v_off, cs_off, ws + w.img, MuReduce{nullptr, nullptr, nullptr, nullptr, nullptr, 0.0f});
+                       w.img_bytes, KP, v_off, cs_off, ws + w.img, MuReduce{nullptr, nullptr, nullptr, nullptr, nullptr, 0.0f}, 1);
 }
 
 // phi + psi for the entry point that takes Q, K, V: two launches (see phi_psi1_kernel).
@@ -512,13 +518,17 @@ static void launch_phi_psi_t(const void *q, Strides3 qs, const void *k, Strides3
     a.qs = qs; a.ks = ks; a.vs = vs;
     a.q_bits = reinterpret_cast<uint32_t *>(ws + w.qbits);
     a.img = ws + w.img; a.amax = amax; a.psum = psum;
-    a.H = s.H; a.N = s.N; a.d = s.d; a.DKP = s.DKP; a.nchunk = s.nchunk; a.nblk = s.nblk;
-    a.img_bytes = w.img_bytes; a.KP = KP;
-    hipLaunchKernelGGL(phi_psi1_kernel<C16>, dim3((unsigned)s.nchunk * s.BH), dim3(PREP_THREADS), 0, stream, a);
+    a.H = s.H; a.N = s.N; a.d = s.d; a.DKP = s.DKP; a.nblk = s.nblk;
+    a.img_bytes = w.img_bytes;
+    hipLaunchKernelGGL(phi_psi1_kernel<C16>, dim3((unsigned)s.nblk * s.BH), dim3(PREP_THREADS), 0, stream, a);
     const MuReduce mr = {psum, mu, mu + s.BH, mu_q_out, mu_k_out, (float)(1.0 / ((double)s.N * (double)s.d))};
-    hipLaunchKernelGGL(v_quant_kernel<C16>, dim3((unsigned)s.nblk * s.BH), dim3(PREP_THREADS), 0, stream,
-                       a.v, vs, static_cast<const uint32_t *>(nullptr), s.H, s.N, s.d, s.DKP, s.nchunk, s.nblk,
-                       amax, delta, w.img_bytes, KP, v_off, cs_off, ws + w.img, mr);
+    // long sequences: several key blocks per workgroup while the grid still fills the chip
+    int bpw = 1;
+    while (bpw < 8 && s.nblk >= 16 * bpw && (int64_t)s.BH * (s.nblk / (2 * bpw)) >= 1024) bpw *= 2;
+    const int ngrp = (s.nblk + bpw - 1) / bpw;
+    hipLaunchKernelGGL(v_quant_kernel<C16>, dim3((unsigned)ngrp * s.BH), dim3(PREP_THREADS), 0, stream,
+                       a.v, vs, static_cast<const uint32_t *>(nullptr), s.H, s.N, s.d, s.DKP, /*partials per head*/ s.nblk,
+                       s.nblk, amax, delta, w.img_bytes, KP, v_off, cs_off, ws + w.img, mr, bpw);
 }
 
 int launch_phi_psi(const void *q, Strides3 qs, const void *k, Strides3 ks, const void *v, Strides3 vs,
