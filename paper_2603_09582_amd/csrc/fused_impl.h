@@ -876,9 +876,6 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
                     fp4_pm1_from_bits8(bits);
             }
         }
-        // accumulator seeds start from the float-bit offset; the V codes add 128 * their sums
-        if (threadIdx.x < nblk * DKP)
-            reinterpret_cast<int *>(imgp(threadIdx.x / DKP) + L::CS_OFF)[threadIdx.x % DKP] = PV_MAGIC_BITS;
         // V: absmax per channel through LDS integer maxima
         if (von) {
             unsigned mb[4] = {0u, 0u, 0u, 0u};
@@ -936,12 +933,9 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
                     quant_quad(vw[kq], kc, packed);
                     char *imgq = imgp(quad / (BV / 4));
                     char *dstv = imgq + L::V_OFF + 4 * (quad % (BV / 4));
-                    int *cs = reinterpret_cast<int *>(imgq + L::CS_OFF);
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
+                    for (int i = 0; i < 8; ++i)
                         *reinterpret_cast<unsigned *>(dstv + (8 * vc + i) * L::VP) = packed[i];
-                        atomicAdd(&cs[8 * vc + i], 128 * __builtin_amdgcn_sdot4((int)packed[i], 0x01010101, 0, false));
-                    }
                 }
             }
         }
@@ -960,6 +954,23 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     }
     wait_vmem();
     __syncthreads();
+    if constexpr (ONEHEAD) {
+        // accumulator seeds of the two images: float-bit offset + 128 * (column sums of the V
+        // codes), one thread per (block, channel) over the finished tiles
+        if ((int)threadIdx.x < p.nblk * DKP) {
+            char *imgq = threadIdx.x / DKP ? bufB : bufA;
+            const int ch = threadIdx.x % DKP;
+            int sum = 0;
+#pragma unroll
+            for (int j = 0; j < BV / 16; ++j) {
+                const u4 x = *reinterpret_cast<const u4 *>(imgq + L::V_OFF + ch * L::VP + 16 * j);
+#pragma unroll
+                for (int n = 0; n < 4; ++n) sum = __builtin_amdgcn_sdot4((int)x[n], 0x01010101, sum, false);
+            }
+            reinterpret_cast<int *>(imgq + L::CS_OFF)[ch] = PV_MAGIC_BITS + 128 * sum;
+        }
+        __syncthreads();
+    }
 
     const char *imgA = bufA + isel * L::BYTES, *imgB = bufB + isel * L::BYTES;
     for (;;) {
