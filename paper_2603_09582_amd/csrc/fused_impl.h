@@ -619,7 +619,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         }
         //    the LDS reads of the P.V phase go out now and land during the exponentials
         v16i acc[DK];
-        v4i va[PRE][KT];
+        v4i va[PRE > 0 ? PRE : 1][KT];
 #pragma unroll
         for (int cb = 0; cb < PRE; ++cb) {
 #pragma unroll
@@ -750,17 +750,6 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         for (int cb = 0; cb < DK; ++cb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) Of[cb][r] = fmaf(Of[cb][r], resc, __int_as_float(acc[cb][r]));
-        //    The carried offset 1.5 * 2^23 * rho sets the carry's rounding unit: it is taken out
-        //    every REBASE blocks (one FMA per output register), so that rho <= REBASE and a block
-        //    result is rounded to at most 8 units of the integer accumulator whatever N is.
-        if ((it & (REBASE - 1)) == REBASE - 1) {
-#pragma unroll
-            for (int cb = 0; cb < DK; ++cb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) Of[cb][r] = fmaf(-PV_MAGIC_F, rho, Of[cb][r]);
-            rho = 0.0f;
-        }
-
         if (TBLK && more)
             tblk_store(tblk + (tpar ^ 1) * TBLK_N, sw ? inv_alpha_of(pend_muq, pend_muk) : inv_alpha);
         __builtin_amdgcn_sched_barrier(0);  // keep the wait at the very end of the block
@@ -973,9 +962,22 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     }
 
     const char *imgA = bufA + isel * L::BYTES, *imgB = bufB + isel * L::BYTES;
+    // The carried offset 1.5 * 2^23 * rho sets the carry's rounding unit: it is taken out once
+    // in REBASE blocks (one FMA per output register), so that rho stays below REBASE + 2 and a
+    // block result is rounded to at most 8 units of the integer accumulator whatever N is.  (At
+    // the loop's back edge: inside the block body the extra branch cost the four-channel-block
+    // kernels their registers.)
+    auto rebase = [&]() {
+#pragma unroll
+        for (int cb = 0; cb < DK; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) Of[cb][r] = fmaf(-PV_MAGIC_F, rho, Of[cb][r]);
+        rho = 0.0f;
+    };
     for (;;) {
         if (!step(imgA, lds_offset(bufB), bA, lds_offset(bB), 0)) break;
         if (!step(imgB, lds_offset(bufA), bB, lds_offset(bA), 1)) break;
+        if (it >= REBASE && (it & (REBASE - 2)) == 0) rebase();  // `it`: the block that comes next
     }
 }
 
