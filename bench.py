@@ -366,6 +366,21 @@ def probe_rows(iters=4096, blocks=256 * 16, reps=3):
             if partner != label:
                 row["with_" + partner] = rate(op | (ba.PROBE_OPS[partner] << 8))
         rows.append(row)
+    # the softmax's own instruction mix on register data, 16 values per lane and step, with the LDS
+    # per workgroup pinned so that 1, 2, 3 or 4 four-wave workgroups fit a compute unit
+    out2 = torch.empty(256 * 16 * 256, dtype=torch.float32, device="cuda")
+    for kib, waves in ((160, 1), (80, 2), (52, 3), (40, 4)):
+        op, blk, it = ba.PROBE_SOFTMAX | (kib << 8), 256 * 4 * waves, 2048
+        ba.probe_valu(op, it, blk, out2)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for e in ev:
+            e[0].record()
+            ba.probe_valu(op, it, blk, out2)
+            e[1].record()
+        torch.cuda.synchronize()
+        ms = statistics.median(a.elapsed_time(c) for a, c in ev)
+        rows.append({"op": "softmax_mix", "waves_per_simd": waves, "lds_kib_per_workgroup": kib,
+                     "t_values_per_s": blk * 256 * 16 * it / (ms * 1e-3) / 1e12})
     return rows
 
 

@@ -388,6 +388,7 @@ def logits_debug(q_bits: torch.Tensor, k_bits: torch.Tensor, d: int, row_begin: 
 PROBE_OPS = {"fma": 0, "exp2": 1, "add": 2, "max3": 3, "cvt_pk_u8": 4, "cvt_f32_i32": 5, "or": 6, "mul": 7,
              "lshl": 8, "and": 9, "xor": 10, "min3_i32": 11, "lshl_add": 12, "mov": 13, "add_u32": 14, "perm": 15}
 PROBE_PARTNERS = ("fma", "cvt_pk_u8", "exp2", "or")
+PROBE_SOFTMAX = 64
 PROBE_CHAINS = 8
 
 
