@@ -428,12 +428,12 @@ def cpu_baseline(x, seconds):
                       f"packing, mu and V quantisation; {t:.1f} s"}
 
 
-def profile_record(workload):
-    """HBM bytes per launch of the fused kernel as the committed rocprofv3 summary of this
-    workload states them (`traffic_bytes_per_launch: <number>`), or None."""
+def profile_record(workload, key="traffic_bytes_per_launch"):
+    """A figure of the fused kernel as the committed rocprofv3 summary of this workload states it
+    (a line `<key>: <number>`): HBM bytes per launch, executed lane-instructions per pair; or None."""
     path = os.path.join(ROOT, "profiles", f"binattn_kernels_{workload}.txt")
     try:
-        m = re.search(r"^traffic_bytes_per_launch\s*:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        m = re.search(r"^" + re.escape(key) + r"\s*:\s*([0-9.eE+]+)", open(path).read(), re.M)
         return float(m.group(1)) if m else None
     except OSError:
         return None
@@ -491,6 +491,12 @@ def main():
                      "frac_strict_count": res["alu_tlaneops"] / ALU_PEAK_TLANEOPS
                                           * ALU_SLOTS_PER_PAIR_STRICT / ALU_SLOTS_PER_PAIR,
                      "strict_lane_instr_per_pair": ALU_SLOTS_PER_PAIR_STRICT,
+                     # what the SIMDs executed (SQ_INSTS_VALU x 64 / pairs, v_exp_f32 counted twice, from the
+                     # committed rocprofv3 summary) and the fraction of the peak that is
+                     "executed_lane_instr_per_pair": profile_record(a.workload, "executed_lane_instr_per_pair"),
+                     "frac_executed": (None if profile_record(a.workload, "executed_lane_instr_per_pair") is None else
+                                       res["alu_tlaneops"] / ALU_PEAK_TLANEOPS
+                                       * profile_record(a.workload, "executed_lane_instr_per_pair") / ALU_SLOTS_PER_PAIR),
                      "algorithmic_hbm_bytes": res["fused_hbm_bytes"]},
         "roofline_other_bounds": {
             "t_valu_ms": bd["t_valu_ms"], "t_hbm_ms": bd["t_hbm_ms"], "t_mfma_ms": bd["t_mfma_ms"],

@@ -20,7 +20,10 @@
  *    arguments are validated before anything is launched, so a failing call
  *    leaves every output untouched.  Inputs are never modified.
  *  - Supported shapes: B, H, N >= 1 with B*H < 2^31 / 128 and N <= 2^24;
- *    d a multiple of 8 with 8 <= d <= 128.
+ *    d a multiple of 8 with 8 <= d <= 128.  Accuracy does not degrade with N: the
+ *    running output of Alg. 1 is carried in fp32 and rounded by at most 4 units of
+ *    the integer P~.V~ scale per 128-key block (against a final divisor of at
+ *    least 255), whatever the number of blocks.
  *  - Q, K, V and the output are bf16; their base pointers must be 16-byte
  *    aligned and every stride a multiple of 8 elements.
  *  - Calls on one stream are ordered; the entry points keep no global mutable

@@ -647,6 +647,44 @@ def test_hip_graph_replay_matches_eager():
     check_close(gpu_out_f64(out)[:, :, ::37], ref, "graph test, last inputs vs O2")
 
 
+def test_hip_graph_replay_of_the_one_call_path_is_bit_identical():
+    # binattn_attention sums the abs-means in a fixed order (no atomics on its path), so a captured
+    # call replays to the same bits as an eager call: three launches, no fill, no memset.
+    B, H, N, d = 2, 2, 2304, 64
+    say("HIP graph capture / replay of binattn_attention")
+    xs = [small_inputs(B, H, N, d, 720 + i) for i in range(3)]
+    q, k, v, bias = (dev(t).clone() for t in (xs[0].q, xs[0].k, xs[0].v, xs[0].bias))
+    out = torch.empty(B, H, N, d, dtype=torch.bfloat16, device="cuda")
+    mq = torch.empty(B, H, dtype=torch.float32, device="cuda")
+    ws = ba.alloc_workspace(B, H, N, d, "cuda")
+
+    def step():
+        ba.attention(q, k, v, bias, xs[0].scale, out=out, workspace=ws, mu_q=mq)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for i in (1, 2, 0, 1):
+        for dst, src in ((q, xs[i].q), (k, xs[i].k), (v, xs[i].v), (bias, xs[i].bias)):
+            dst.copy_(dev(src))
+        out.zero_()
+        mq.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed, mu_replayed = out.clone(), mq.clone()
+        step()
+        torch.cuda.synchronize()
+        assert torch.equal(replayed, out) and torch.equal(mu_replayed, mq), f"replay with inputs {i} differs from eager"
+    ref = oracle_forward(xs[1], xs[1].bias, rows=np.arange(0, N, 37))["O2"]
+    check_close(gpu_out_f64(out)[:, :, ::37], ref, "graph test (one call), last inputs vs O2")
+
+
 # ---- the single-launch form for short sequences -------------------------------------------
 FUSED_SHAPES = [(1, 2, 1, 64), (1, 2, 2, 8), (2, 1, 63, 64), (1, 2, 64, 72), (1, 1, 65, 128), (1, 3, 129, 64),
                 (2, 2, 197, 64), (1, 2, 255, 72), (3, 2, 256, 72), (1, 1, 256, 128), (1, 2, 136, 96),
