@@ -384,6 +384,24 @@ def probe_rows(iters=4096, blocks=256 * 16, reps=3):
     return rows
 
 
+def clock_from_probe():
+    """Shader clock under a pure vector load, from the issue-rate probe: a dependent-free stream of
+    v_fma_f32 at full occupancy issues one instruction per SIMD and 4 clocks, so lane-instructions/s
+    / (256 CUs x 4 SIMDs x 16 lanes) is the clock the chip held (an estimate from below)."""
+    import torch
+    from paper_2603_09582_amd import binding as ba
+    blocks, iters = 256 * 16, 2048
+    out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    op = ba.PROBE_OPS["fma"] * 0x101
+    ba.probe_valu(op, iters, blocks, out)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    ba.probe_valu(op, iters, blocks, out)
+    e1.record()
+    torch.cuda.synchronize()
+    return blocks * 256 * ba.PROBE_CHAINS * iters / (e0.elapsed_time(e1) * 1e-3) / (256 * 4 * 16) / 1e9
+
+
 def cpu_baseline(x, seconds):
     """Time the oracle (as it stands) on a bounded sample of this workload: query rows of head
     (0, 0), and once a whole head takes less than the budget, further whole heads."""
@@ -503,7 +521,7 @@ def main():
             "t_bound_ms": bd["t_bound_fused_ms"], "frac_of_t_bound": bd["t_bound_fused_ms"] / res["fused_ms"],
             "mfma_int8_frac": res["mfma_tops_algorithmic"] / MFMA_I8_PEAK_TOPS,
             "hbm_frac": res["fused_hbm_gbs"] / HBM_PEAK_GBS, "hbm_gbs": res["fused_hbm_gbs"]},
-        "clocks": clocks,
+        "clocks": {"rocm_smi_before_the_run": clocks, "ghz_under_a_v_fma_stream": clock_from_probe()},
     }
     del x
     torch.cuda.empty_cache()

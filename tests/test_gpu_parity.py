@@ -997,7 +997,8 @@ def test_relpos_table_at_the_128x128_grid_sampled_rows():
 
 
 @pytest.mark.parametrize("B,H,N,d,kind", [(2, 1, 16384, 64, "one_hot"), (2, 1, 16384, 64, "few_visible"),
-                                          (1, 1, 32768, 128, "one_hot"), (1, 1, 16384, 72, "few_visible")])
+                                          (1, 1, 32768, 128, "one_hot"), (1, 1, 16384, 72, "few_visible"),
+                                          (2, 1, 65536, 64, "one_hot"), (2, 1, 65536, 64, "diffuse")])
 def test_peaked_rows_at_long_sequences(B, H, N, d, kind):
     # Rows whose whole weight sits on a few EARLY keys: every later block adds (almost) nothing
     # to a carry that must survive more than a hundred rescale steps unharmed.  Compared with
@@ -1010,6 +1011,11 @@ def test_peaked_rows_at_long_sequences(B, H, N, d, kind):
     if kind == "one_hot":        # +50 on one key among the first hundred
         star = (torch.arange(N, device="cuda") * 7 + 3) % 100
         bias[:, torch.arange(N, device="cuda"), star] = 50.0
+    elif kind == "diffuse":      # flat rows over 512 key blocks: the carry sums half a million terms
+        gen = torch.Generator(device="cuda").manual_seed(N + d)
+        for h in range(H):
+            for r0 in range(0, N, 4096):
+                bias[h, r0:r0 + 4096] = (torch.randn(4096, N, generator=gen, device="cuda") * 0.02).to(torch.bfloat16)
     else:                        # everything masked but five early keys
         bias.fill_(float("-inf"))
         bias[:, :, 3:8] = torch.tensor([0.5, -1.0, 2.0, 0.0, 1.0], dtype=torch.bfloat16, device="cuda")
