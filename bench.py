@@ -300,6 +300,15 @@ def config_row(name, steps=CONFIG_STEPS, warmup=CONFIG_WARMUP):
                                 "tops_equiv": w.equiv_ops / (statistics.median(per1) * 1e-3) / 1e12,
                                 "t_bound_ms": bd["t_bound_single_launch_ms"],
                                 "frac_of_bound": bd["t_bound_single_launch_ms"] / statistics.median(per1)}
+    # the fastest way through the library for this configuration, against that path's own bound
+    cands = [("pack_qk + prepare_kv + attend", row["ms_per_step"]["median"], row["step_frac_of_bound"])]
+    if "one_call" in row:
+        cands.append(("binattn_attention (three launches)", row["one_call"]["ms_per_step"]["median"], row["one_call"]["frac_of_bound"]))
+    if "single_launch" in row:
+        cands.append(("binattn_forward_fused (one launch)", row["single_launch"]["ms_per_step"]["median"], row["single_launch"]["frac_of_bound"]))
+    best = min(cands, key=lambda c: c[1])
+    row["best"] = {"path": best[0], "ms_per_step": best[1], "frac_of_bound": best[2],
+                   "tops_equiv": w.equiv_ops / (best[1] * 1e-3) / 1e12}
     del b
     torch.cuda.empty_cache()
     return row
