@@ -88,16 +88,23 @@ __device__ __forceinline__ unsigned lds_offset(const void *p) {
     return (unsigned)(size_t)(__attribute__((address_space(3))) const char *)p;
 }
 
+// A pointer that is the same in every lane, moved into scalar registers.
+template <class T>
+__device__ __forceinline__ const T *uniform_ptr(const T *p) {
+    const uint64_t a = reinterpret_cast<uint64_t>(p);
+    // (the builtin returns int: widen through unsigned, or the low half is sign-extended)
+    const uint64_t u = (uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)a) |
+                       ((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)(a >> 32)) << 32);
+    return reinterpret_cast<const T *>(u);
+}
+
 // One asynchronous 16-byte-per-lane copy global -> LDS: lane L's 16 bytes, read from
 // sbase + voff (sbase wave-uniform, kept in scalar registers; voff this lane's byte offset),
 // land at lds_base + 16 L (lds_base wave-uniform).  Issued through inline assembly so that
 // the compiler does not serialise later LDS reads of OTHER buffers against it; the callers
 // order it by hand (wait_vmem + barrier before the data is read).
 __device__ __forceinline__ void dma16(const void *sbase, unsigned voff, unsigned lds_base) {
-    const uint64_t a = reinterpret_cast<uint64_t>(sbase);
-    // (the builtin returns int: widen through unsigned, or the low half is sign-extended)
-    const uint64_t u = (uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)a) |
-                       ((uint64_t)(unsigned)__builtin_amdgcn_readfirstlane((unsigned)(a >> 32)) << 32);
+    const uint64_t u = reinterpret_cast<uint64_t>(uniform_ptr(static_cast<const char *>(sbase)));
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(voff), "s"(u)

@@ -249,14 +249,14 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
             const int r = (lane >> 3) ^ (rg & 1);
             const int row0 = min(t.rb * BR + wave * ROWS_PER_WAVE + 8 * rg, N - 1);  // uniform
             const int row = min(row0 + r, N - 1);
-            o.base[j] = static_cast<const char *>(p.bias) +
-                        ((int64_t)t.b * p.bs.b + (int64_t)t.h * p.bs.h + (int64_t)row0 * p.bs.n) * 2;
+            o.base[j] = uniform_ptr(static_cast<const char *>(p.bias) +
+                                    ((int64_t)t.b * p.bs.b + (int64_t)t.h * p.bs.h + (int64_t)row0 * p.bs.n) * 2);
             o.voff[j] = (unsigned)(row - row0) * (unsigned)p.bs.n * 2u + 16u * dma_c[j];
         }
         return o;
     };
     auto image_ptr = [&](const Item &t) -> const char * {
-        return p.img + (int64_t)t.bh * p.nblk * L::BYTES;
+        return uniform_ptr(p.img + (int64_t)t.bh * p.nblk * L::BYTES);
     };
     // turn the fetched registers into the item's state
     auto begin_item = [&](const Item &t) {
@@ -538,9 +538,17 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         }
         // 1. all LDS reads of the logit phase go out together: bias tile, key rows
         if (LDS_BIAS) {
-            const char *row = bbuf + ((m >> 3) * 2 + g) * 1024 + 128 * ((m & 7) ^ ((m >> 3) & 1));
+            // chunk i of this lane's row sits at row + 16 (i ^ (m & 7)) = (row + 16 (m & 7)) ^ 16 i (rows are
+            // 128-byte aligned); the lane number is made opaque so that the addresses are formed here
+            // instead of being carried through the block loop in eight registers per buffer
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
+            const int mm = ln & 31, gg = ln >> 5;
+            const unsigned a0 = lds_offset(bbuf) + ((mm >> 3) * 2 + gg) * 1024 +
+                                128 * ((mm & 7) ^ ((mm >> 3) & 1)) + 16 * (mm & 7);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) braw[i] = *reinterpret_cast<const u4v *>(row + 16 * (i ^ (m & 7)));
+            for (int i = 0; i < 8; ++i)
+                braw[i] = *reinterpret_cast<const __attribute__((address_space(3))) u4v *>((size_t)(a0 ^ (16u * i)));
         }
         v4i ka[KT][DK2];
 #pragma unroll
