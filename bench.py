@@ -300,6 +300,13 @@ def config_row(name, steps=CONFIG_STEPS, warmup=CONFIG_WARMUP):
                                 "tops_equiv": w.equiv_ops / (statistics.median(per1) * 1e-3) / 1e12,
                                 "t_bound_ms": bd["t_bound_single_launch_ms"],
                                 "frac_of_bound": bd["t_bound_single_launch_ms"] / statistics.median(per1)}
+        if w.B * w.H > 256:   # more heads than compute units: 4-wave workgroups by default; the 8-wave form beside it
+            row["single_launch"]["workgroups"] = "4 waves, two per compute unit"
+            one8 = lambda i: ba.forward_fused(x.q, x.k, x.v, x.bias, x.scale, out=b.out, flags=ba.FLAG_WIDE8)
+            _, per8 = timed(one8, steps, warmup)
+            row["single_launch"]["ms_per_step_8_wave_form"] = med_min(per8)
+        else:
+            row["single_launch"]["workgroups"] = "8 waves, one per head"
     # the fastest way through the library for this configuration, against that path's own bound
     cands = [("pack_qk + prepare_kv + attend", row["ms_per_step"]["median"], row["step_frac_of_bound"])]
     if "one_call" in row:

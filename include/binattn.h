@@ -61,12 +61,16 @@ enum { BINATTN_BIAS_BF16 = 1, BINATTN_BIAS_F32 = 2 };
 enum {
     BINATTN_FLAG_NO_MU = 1,   /* ignore mu_q, mu_k (ablation row "no scale", Tab. 5) */
     BINATTN_FLAG_NO_BIAS = 2, /* ignore bias (ablation rows without bias, Tab. 5)    */
-    BINATTN_FLAG_LUT = 4      /* bias-free calls only: read 255 exp(S - m) from a per-head table
+    BINATTN_FLAG_LUT = 4,     /* bias-free calls only: read 255 exp(S - m) from a per-head table
                                  of its d + 1 possible values instead of computing every
                                  exponential.  Same results up to the rounding of one fp32
                                  exponential; measured slower than the exponentials on MI355X
                                  (the table read costs more than the FMA + v_exp_f32 it
                                  replaces), so it is opt-in and kept for comparison         */
+    BINATTN_FLAG_WIDE8 = 8,   /* single-launch forms only: one 8-wave workgroup per head even
+                                 when the call has more heads than the chip has compute units
+                                 (by default such calls use 4-wave workgroups, two per compute
+                                 unit).  Same results; kept for comparison                    */
 };
 
 /* variants of binattn_logits_debug */

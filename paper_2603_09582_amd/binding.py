@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbinattn.so")
 
 BIAS_BF16, BIAS_F32 = 1, 2
-FLAG_NO_MU, FLAG_NO_BIAS, FLAG_LUT = 1, 2, 4
+FLAG_NO_MU, FLAG_NO_BIAS, FLAG_LUT, FLAG_WIDE8 = 1, 2, 4, 8
 LOGITS_POPCOUNT, LOGITS_MFMA_I8, LOGITS_MFMA_FP4 = 0, 1, 2
 LOGITS_ROWSUM = 0x100
 

@@ -1,5 +1,6 @@
 // C ABI of libbinattn: argument validation (before anything is launched) and
 // the launch sequences.  See include/binattn.h for the contract.
+#include <cstdlib>
 #include "binattn_internal.h"
 
 #include <mutex>
@@ -246,9 +247,12 @@ int attend_impl(const uint32_t *q_bits, const float *mu_q, const float *mu_k, co
         p.xv = static_cast<const uint16_t *>(raw->v);
         p.xqs = raw->qs; p.xks = raw->ks; p.xvs = raw->vs;
         p.mu_q_out = raw->mu_q_out; p.mu_k_out = raw->mu_k_out;
-        p.wide = 1;
-        p.nrb = 1;
-        p.nb = 2;
+        // More heads than compute units: 4-wave workgroups, two per compute unit, each taking
+        // the head's two row blocks in turn; otherwise one 8-wave workgroup per head.
+        const bool four = B * H > ONEHEAD4_MIN_HEADS && onehead4_built(s.DK, mode) && !(flags & BINATTN_FLAG_WIDE8);
+        p.wide = four ? 3 : 1;
+        p.nrb = four ? (N + BR - 1) / BR : 1;
+        p.nb = four ? 1 : 2;
         p.total_wg = B * H;
         switch (s.DK) {
             case 1: return launch_onehead_dk<1>(p, mode, st);

@@ -179,7 +179,7 @@ struct FusedParams {
     const float *delta;
     int B, H, N, d, nblk, nrb, total_wg;
     int nb;              // batch entries per workgroup (1 or 2)
-    int wide;            // 0, or 2: 8-wave workgroups over row-block pairs (nrb counts pairs)
+    int wide;            // 0; 1 / 3: single-launch forms (8 / 4 waves); 2: 8-wave workgroups over row-block pairs (nrb counts pairs)
     // single-launch short-sequence kernel: the bf16 inputs, whether mu is applied, optional mu exports
     const uint16_t *xq, *xk, *xv;
     Strides3 xqs, xks, xvs;
@@ -194,6 +194,13 @@ struct FusedParams {
 template <int DK>
 int launch_fused_dk(const FusedParams &p, int mode, hipStream_t stream);
 // The single-launch form for at most two key blocks (nb must be 2, total_wg = B * H).
+// single-launch form: calls with more heads than this use 4-wave workgroups (two per compute unit)
+constexpr int ONEHEAD4_MIN_HEADS = 256;
+// ... in the variants whose 256-thread prologue holds a head's loads in registers without spilling
+constexpr bool onehead4_built(int DK, int mode) {
+    return DK <= 2 || (DK == 3 && (mode == BIAS_NONE || mode == BIAS_F32_VEC || mode == BIAS_BF16_LDS || mode == BIAS_AXIAL));
+}
+
 template <int DK>
 int launch_onehead_dk(const FusedParams &p, int mode, hipStream_t stream);
 

@@ -83,12 +83,19 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
 // 4-wave workgroups with bias tiles (d > 96): the two halves of the workgroup are the row
 // blocks 2 rp, 2 rp + 1 of ONE (batch, head); they share the operand images (one copy stream
 // for 256 rows) and keep private bias tiles; the grid is persistent as with NB = 1.
-enum { WIDE_NONE = 0, WIDE_ONEHEAD = 1, WIDE_ROWS2 = 2 };
+//
+// ONEHEAD4 (4 waves) is the single-launch form for launches with more heads than compute units:
+// the same prologue with 256 threads, then the head's two 128-row blocks one after the other
+// as two items of the persistent stream (the images stay where they are).  Two such workgroups
+// share a compute unit, so one head's loads and preparation overlap the other's block loop.
+enum { WIDE_NONE = 0, WIDE_ONEHEAD = 1, WIDE_ROWS2 = 2, WIDE_ONEHEAD4 = 3 };
 template <int DK, int MODE, int NB, int WIDE = WIDE_NONE>
 __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const FusedParams p) {
     using L = Image<DK>;
-    constexpr bool ONEHEAD = WIDE == WIDE_ONEHEAD, ROWS2 = WIDE == WIDE_ROWS2;
-    static_assert(WIDE == WIDE_NONE || NB == 2, "the wide forms use 8 waves");
+    constexpr bool ONEHEAD4 = WIDE == WIDE_ONEHEAD4;
+    constexpr bool ONEHEAD = WIDE == WIDE_ONEHEAD || ONEHEAD4, ROWS2 = WIDE == WIDE_ROWS2;
+    static_assert(WIDE == WIDE_NONE || ONEHEAD4 || NB == 2, "the wide forms use 8 waves");
+    static_assert(!ONEHEAD4 || NB == 1, "the 4-wave single-launch form");
     constexpr bool PAIR = NB == 2 && WIDE == WIDE_NONE;  // two batch entries sharing bias tiles
     constexpr int NWI = ROWS2 ? 8 : 4;                   // waves that copy one operand image
     constexpr int NIMG = PAIR ? 2 : 1;          // operand images per buffer
@@ -107,7 +114,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     __shared__ __attribute__((aligned(1024))) char bufB[NIMG * L::BYTES];
     // BIAS_BF16_LDS: staging of the 32 x 128 bias tiles, 8 KiB per 32-row group.
     // NB = 1: one region per wave, private to it.  NB = 2: two buffers shared by the pair.
-    __shared__ __attribute__((aligned(1024))) char biasA[LDS_BIAS ? (WIDE != WIDE_NONE ? 8 : 4) * 8192 : 1024];
+    __shared__ __attribute__((aligned(1024))) char biasA[LDS_BIAS ? (NB == 2 && WIDE != WIDE_NONE ? 8 : 4) * 8192 : 1024];
     __shared__ __attribute__((aligned(1024))) char biasB[BIAS_DB ? 4 * 8192 : 1024];
     // BIAS_AXIAL: the head's two relative-position tables, already divided by alpha.
     //   axu: four copies of the REVERSED x table, copy j shifted by j entries, so that every
@@ -157,7 +164,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     const int wave = __builtin_amdgcn_readfirstlane((threadIdx.x >> 6) & 3);  // 32-row group
     const int bsel = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);        // half of the workgroup
     const int isel = PAIR ? bsel : 0;                // which resident image / delta copy
-    const int wreg = WIDE != WIDE_NONE ? 4 * bsel + wave : wave;  // this wave's private bias region / copy share
+    const int wreg = (NB == 2 && WIDE != WIDE_NONE) ? 4 * bsel + wave : wave;  // this wave's private bias region / copy share
     const int m = lane & 31, g = lane >> 5;
     const int N = p.N, d = p.d, W = (d + 31) / 32;
     const int nbp = p.B / NIMG;
@@ -175,11 +182,15 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     };
     auto decode = [&](int v) -> Item {
         Item t;
+        // (ONEHEAD4: ids v, v + grid size are the two row blocks of one head; grid size = vmax)
+        const int j4 = ONEHEAD4 ? (v >= 2 * vmax ? 2 : v >= vmax ? 1 : 0) : 0;
+        if (ONEHEAD4) v -= j4 * vmax;
         const int u = (v & 7) * per_xcd + (v >> 3);
         t.valid = v < vmax && u < p.total_wg;
+        if (ONEHEAD4) t.valid = t.valid && j4 < p.nrb;
         const int uu = t.valid ? u : 0;
         t.b = ONEHEAD ? uu / p.H : (uu % nbp) * NIMG + isel;
-        t.rb = ONEHEAD ? bsel : ROWS2 ? 2 * ((uu / nbp) % p.nrb) + bsel : (uu / nbp) % p.nrb;
+        t.rb = ONEHEAD4 ? j4 : ONEHEAD ? bsel : ROWS2 ? 2 * ((uu / nbp) % p.nrb) + bsel : (uu / nbp) % p.nrb;
         t.h = ONEHEAD ? uu % p.H : uu / (nbp * p.nrb);
         t.bh = t.b * p.H + t.h;
         return t;
@@ -226,8 +237,14 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
 
     // registers fetched ahead for the NEXT item
     unsigned pend_q[2 * DK2];
+    unsigned pend_q2[ONEHEAD4 ? 2 * DK2 : 1];  // ONEHEAD4: sign words of this lane's row in the second row block
     float pend_muq = 1.0f, pend_muk = 1.0f;
     auto fetch_item_regs = [&](const Item &t) {
+        if constexpr (ONEHEAD4) {  // made by the prologue
+#pragma unroll
+            for (int w = 0; w < 2 * DK2; ++w) pend_q[w] = pend_q2[w];
+            return;
+        }
         const int qc = min(t.rb * BR + wave * ROWS_PER_WAVE + m, N - 1);
         const uint32_t *qw = p.q_bits + ((int64_t)t.bh * N + qc) * W;
 #pragma unroll
@@ -775,7 +792,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         nxt = decode(v + gridDim.x);
         begin_item(cur);
         it = 0;
-        parity ^= 1;
+        if (!ONEHEAD4) parity ^= 1;  // (the single-launch forms keep one copy of delta_v)
         return true;
     };
 
@@ -804,13 +821,29 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         // 64 s + 32 g + 8 j); addresses are clamped into the row, unused chunks are skipped below
         const int qrow = cur.rb * BR + wave * ROWS_PER_WAVE + m;
         u4 qx[DK2][4];
+        float qsum = 0.0f;
+        auto load_q_row = [&](int row) {
 #pragma unroll
-        for (int sI = 0; sI < DK2; ++sI)
+            for (int sI = 0; sI < DK2; ++sI)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int c0 = 32 * (2 * sI + g) + 8 * j;
-                qx[sI][j] = *reinterpret_cast<const u4 *>(qb_ + (int64_t)min(qrow, N - 1) * p.xqs.n + (c0 < d ? c0 : 0));
+                for (int j = 0; j < 4; ++j) {
+                    const int c0 = 32 * (2 * sI + g) + 8 * j;
+                    qx[sI][j] = *reinterpret_cast<const u4 *>(qb_ + (int64_t)min(row, N - 1) * p.xqs.n + (c0 < d ? c0 : 0));
+                }
+        };
+        auto q_row_words = [&](int row, unsigned *words) {  // sign words of the loaded row, |q| into qsum
+#pragma unroll
+            for (int w = 0; w < 2 * DK2; ++w) words[w] = 0u;
+#pragma unroll
+            for (int sI = 0; sI < DK2; ++sI) {
+                unsigned word = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (row < N && 32 * (2 * sI + g) + 8 * j < d) word |= sign_bits8_abs(qx[sI][j], qsum) << (8 * j);
+                if (g) words[2 * sI + 1] = word; else words[2 * sI] = word;
             }
+        };
+        load_q_row(qrow);
         // V rows into registers: a thread owns quads of consecutive tokens of one 8-channel
         // chunk; consecutive lanes take consecutive chunks (whole-row loads)
         // i / C16 for 0 <= i < 2^12 and C16 <= 16 without the integer-division sequence:
@@ -823,10 +856,13 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         const bool von = vr < RT;
         // (loads are unconditional from clamped rows and masked where they are used: a load
         // under a condition makes the compiler wait for it on the spot)
-        u4 vw[2][4];
+        // (token quads per pass: 512 threads cover the 64 quads of two key blocks in two passes
+        // for every head dimension, 256 threads in at most four)
+        constexpr int KQ = NB == 2 ? 2 : 4;
+        u4 vw[KQ][4];
         auto v_row_on = [&](int kq, int t) { return von && 4 * (vr + kq * RT) + t < N && vr + kq * RT < 2 * BV / 4; };
 #pragma unroll
-        for (int kq = 0; kq < 2; ++kq)
+        for (int kq = 0; kq < KQ; ++kq)
 #pragma unroll
             for (int t = 0; t < 4; ++t)
                 vw[kq][t] = *reinterpret_cast<const u4 *>(vb_ + (int64_t)min(4 * (vr + kq * RT) + t, N - 1) * p.xvs.n + 8 * vc);
@@ -847,17 +883,10 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         }
         if (threadIdx.x < DKP) sabs[threadIdx.x] = 0;
         // the sign words of the query row (the oldest loads: V and K may still be in flight)
-        float qsum = 0.0f;
-#pragma unroll
-        for (int w = 0; w < 2 * DK2; ++w) pend_q[w] = 0u;
-#pragma unroll
-        for (int sI = 0; sI < DK2; ++sI) {
-            unsigned word = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (qrow < N && 32 * (2 * sI + g) + 8 * j < d) word |= sign_bits8_abs(qx[sI][j], qsum) << (8 * j);
-            if (g) pend_q[2 * sI + 1] = word; else pend_q[2 * sI] = word;
-        }
+        q_row_words(qrow, pend_q);
+        // (ONEHEAD4: the lane's row in the second row block takes the same registers; its loads
+        // land during the key phase below)
+        if constexpr (ONEHEAD4) load_q_row(qrow + BR);
         __syncthreads();
         // keys: sign bits -> FP4 codes of +-1 at the row position the QK tile reads
         float ksum = 0.0f;
@@ -873,11 +902,12 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
                     fp4_pm1_from_bits8(bits);
             }
         }
+        if constexpr (ONEHEAD4) q_row_words(qrow + BR, pend_q2);
         // V: absmax per channel through LDS integer maxima
         if (von) {
             unsigned mb[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int kq = 0; kq < 2; ++kq)
+            for (int kq = 0; kq < KQ; ++kq)
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     if (!v_row_on(kq, t)) vw[kq][t] = u4{0u, 0u, 0u, 0u};  // rows beyond N: code 0
@@ -923,7 +953,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
         if (von) {
             const QuantConsts8 kc = load_quant_consts8(&sdelta[0][0][0], srlo, srhi, vc);
 #pragma unroll
-            for (int kq = 0; kq < 2; ++kq) {
+            for (int kq = 0; kq < KQ; ++kq) {
                 const int quad = vr + kq * RT;
                 if (4 * quad < N && quad < 2 * BV / 4) {
                     unsigned packed[8];
@@ -1033,6 +1063,22 @@ int launch_fused_dk(const FusedParams &p, int mode, hipStream_t stream) {
 template <int DK>
 int launch_onehead_dk(const FusedParams &p, int mode, hipStream_t stream) {
     const int needed = ((p.total_wg + 7) / 8) * 8;
+    if (p.nb == 1) {  // 4-wave form: the variants onehead4_built() names
+        const dim3 grid((unsigned)needed), block(FUSED_THREADS);
+#define CASE(M)                                                                                          \
+    case M:                                                                                              \
+        if constexpr (onehead4_built(DK, M)) {                                                           \
+            hipLaunchKernelGGL((fused_kernel<DK, M, 1, WIDE_ONEHEAD4>), grid, block, 0, stream, p);     \
+            return check_launch();                                                                       \
+        }                                                                                                \
+        return BINATTN_ERR_SHAPE;
+        switch (mode) {
+            CASE(BIAS_NONE) CASE(BIAS_LUT) CASE(BIAS_BF16_VEC) CASE(BIAS_F32_VEC) CASE(BIAS_AXIAL) CASE(BIAS_TABLE)
+            CASE(BIAS_BF16_LDS)
+            default: return BINATTN_ERR_DTYPE;
+        }
+#undef CASE
+    }
     const dim3 grid((unsigned)needed), block(FUSED_THREADS * 2);
     switch (mode) {
 #define CASE(M) case M: hipLaunchKernelGGL((fused_kernel<DK, M, 2, WIDE_ONEHEAD>), grid, block, 0, stream, p); break;

@@ -782,6 +782,80 @@ def test_forward_fused_more_heads_than_cus(layout):
     assert np.abs(got - run_forward(x, x.bias)).max() <= 2e-3
 
 
+# More heads than compute units: 4-wave workgroups that take a head's two row blocks in turn.
+FUSED4_SHAPES = [(1, 260, 1, 64), (2, 130, 63, 64), (1, 264, 128, 32), (1, 260, 129, 64), (2, 140, 197, 64),
+                 (1, 258, 255, 72), (1, 257, 256, 72), (1, 260, 136, 96), (1, 260, 200, 16), (1, 257, 256, 64)]
+
+
+@pytest.mark.parametrize("B,H,N,d", FUSED4_SHAPES)
+def test_forward_fused_four_wave_form_matches_oracle(B, H, N, d):
+    say(f"single-launch forward, 4-wave form, B={B} H={H} N={N} d={d}")
+    x = small_inputs(B, H, N, d, 900 + N + d)
+    mq = torch.zeros(B, H, dtype=torch.float32, device="cuda")
+    mk = torch.zeros_like(mq)
+    out = ba.forward_fused(dev(x.q), dev(x.k), dev(x.v), dev(x.bias), x.scale, mu_q=mq, mu_k=mk)
+    torch.cuda.synchronize()
+    got = gpu_out_f64(out)
+    for b in range(B):
+        for h in range(0, H, 17):
+            assert float(mq[b, h]) == pytest.approx(orc.abs_mean(np_bits(x.q[b, h])), rel=2e-6)
+            assert float(mk[b, h]) == pytest.approx(orc.abs_mean(np_bits(x.k[b, h])), rel=2e-6)
+    check_close(got, oracle_forward(x, x.bias)["O2"], "out vs O2")
+    # the 8-wave form on the same inputs
+    wide = ba.forward_fused(dev(x.q), dev(x.k), dev(x.v), dev(x.bias), x.scale, flags=ba.FLAG_WIDE8)
+    torch.cuda.synchronize()
+    assert np.abs(got - gpu_out_f64(wide)).max() <= 2e-3
+
+
+@pytest.mark.parametrize("kind", ["none", "f32", "bf16_per_batch", "bf16_odd_rows", "no_mu", "lut", "masked"])
+@pytest.mark.parametrize("d", [64, 72])
+def test_forward_fused_four_wave_form_modes(kind, d):
+    B, H, N = 2, 130, 200
+    say(f"single-launch forward, 4-wave form, d={d}, mode {kind}")
+    x = small_inputs(B, H, N, d, 78)
+    g = torch.Generator().manual_seed(6)
+    bias, flags, use_mu, obias = dev(x.bias), 0, True, x.bias
+    if kind == "none":
+        bias = obias = None
+    elif kind == "f32":
+        obias = torch.randn(H, N, N, generator=g) * 0.3
+        bias = dev(obias)
+    elif kind == "bf16_per_batch":
+        obias = (torch.randn(B, H, N, N, generator=g) * 0.3).to(torch.bfloat16)
+        bias = dev(obias)
+    elif kind == "bf16_odd_rows":                # rows of 201 elements: loaded into registers, not staged
+        store = torch.zeros(H, N, 201, dtype=torch.bfloat16, device="cuda")
+        store[:, :, :N] = dev(x.bias)
+        bias = store[:, :, :N]
+    elif kind == "no_mu":
+        flags, use_mu = ba.FLAG_NO_MU, False
+    elif kind == "lut":
+        flags, bias, obias = ba.FLAG_LUT, None, None
+    elif kind == "masked":
+        obias = x.bias.clone()
+        obias[:, :, :130] = float("-inf")        # the whole first key block and two more keys
+        obias[torch.rand(H, N, N, generator=g) < 0.02] = float("-inf")
+        obias[:, :, 199] = 0.0                   # one key stays visible in every row
+        bias = dev(obias)
+    out = ba.forward_fused(dev(x.q), dev(x.k), dev(x.v), bias, x.scale, flags=flags)
+    torch.cuda.synchronize()
+    got = gpu_out_f64(out)
+    assert np.isfinite(got).all()
+    check_close(got, oracle_forward(x, obias, use_mu=use_mu)["O2"], f"{kind}: out vs O2")
+
+
+@pytest.mark.parametrize("B,H,Gy,Gx,d", [(2, 130, 16, 16, 64), (1, 260, 12, 16, 72), (1, 258, 5, 32, 32)])
+def test_forward_fused_relpos_four_wave_form(B, H, Gy, Gx, d):
+    N = Gy * Gx
+    say(f"single-launch forward, 4-wave form, relative-position table {Gy}x{Gx}, d={d}")
+    x = small_inputs(B, H, N, d, 500 + N)
+    g = torch.Generator().manual_seed(9)
+    table = torch.randn(H, 2 * Gy - 1, 2 * Gx - 1, generator=g) * 0.3
+    out = ba.forward_fused_relpos(dev(x.q), dev(x.k), dev(x.v), dev(table), x.scale)
+    torch.cuda.synchronize()
+    check_close(gpu_out_f64(out), oracle_forward(x, relpos_dense(table, Gy, Gx))["O2"], "out vs O2")
+
+
 # ---- the one-call entry point from the bf16 tensors -------------------------------------------
 @pytest.mark.parametrize("B,H,N,d", [(2, 2, 197, 64), (1, 2, 257, 72), (2, 1, 384, 64), (1, 3, 520, 128), (4, 1, 1160, 32),
                                      (1, 2, 1024, 72), (3, 1, 1160, 104), (1, 1, 2304, 8), (2, 2, 700, 96)])
