@@ -74,6 +74,8 @@ def parse():
                     help="also time the three integer-logit variants of binattn_logits_debug (extra field)")
     ap.add_argument("--probe", action="store_true",
                     help="also measure the issue rate of the softmax's vector-ALU instructions (extra field)")
+    ap.add_argument("--heads", action="store_true",
+                    help="also time the two single-launch forms (8-wave / 4-wave workgroups) over the number of heads (extra field)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bias", action="store_true", help="run without the bias term (not the headline config)")
     ap.add_argument("--lut", action="store_true",
@@ -319,6 +321,34 @@ def config_row(name, steps=CONFIG_STEPS, warmup=CONFIG_WARMUP):
     del b
     torch.cuda.empty_cache()
     return row
+
+
+def heads_rows(launches=60):
+    """binattn_forward_fused with one 8-wave workgroup per head (BINATTN_FLAG_WIDE8) and with 4-wave
+    workgroups (the default above 256 heads) over a range of head counts; microseconds per launch,
+    events around `launches` back-to-back calls."""
+    import torch
+    from paper_2603_09582_amd import binding as ba
+    from paper_2603_09582_amd import workloads as wl
+    rows = []
+    for (B, H, N, d) in [(18, 16, 256, 72), (24, 16, 256, 72), (32, 16, 256, 72), (48, 16, 256, 72), (64, 16, 256, 72),
+                         (24, 12, 197, 64), (43, 12, 197, 64), (64, 12, 197, 64), (128, 12, 197, 64), (32, 16, 128, 64)]:
+        x = wl.make_inputs(wl.custom_workload(B, H, N, d, 7), device="cuda")
+        out = torch.empty_like(x.v)
+        us = []
+        for flags in (ba.FLAG_WIDE8, 0):
+            for _ in range(5):
+                ba.forward_fused(x.q, x.k, x.v, x.bias, x.scale, out=out, flags=flags)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(launches):
+                ba.forward_fused(x.q, x.k, x.v, x.bias, x.scale, out=out, flags=flags)
+            e1.record()
+            torch.cuda.synchronize()
+            us.append(e0.elapsed_time(e1) * 1e3 / launches)
+        rows.append({"heads": B * H, "N": N, "d": d, "us_8_wave_form": us[0], "us_4_wave_form": us[1]})
+        del x, out
+    return rows
 
 
 def logits_rows(steps=20):
@@ -604,6 +634,8 @@ def main():
         line["logits_variants"] = logits_rows()
     if a.probe:
         line["valu_issue_rates"] = probe_rows()
+    if a.heads:
+        line["single_launch_forms_vs_heads"] = heads_rows()
     if a.no_bias:
         line["config"]["workload"] += (" -- WITHOUT bias (diagnostic run), exponentials "
                                        + ("from the per-head table" if a.lut else "computed"))
