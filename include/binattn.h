@@ -232,7 +232,10 @@ int binattn_forward_relpos(const uint32_t *q_bits, const uint32_t *k_bits, const
  *   mu_q_out,
  *   mu_k_out   : optional (may be NULL) float32 [B, H]: the abs-means that were used.
  * Results equal binattn_pack_qk + binattn_forward up to the summation order of the
- * abs-means.  N > 256 returns BINATTN_ERR_SHAPE.
+ * abs-means.  N > 256 returns BINATTN_ERR_SHAPE.  A call with more than 256 (batch, head)
+ * pairs runs 4-wave workgroups, two per compute unit, each taking a head's two 128-row
+ * blocks in turn (BINATTN_FLAG_WIDE8 keeps one 8-wave workgroup per head; same results up
+ * to the summation order of the abs-means).
  */
 int binattn_forward_fused(const void *q, const void *k, const void *v, const int64_t q_strides[3],
                           const int64_t k_strides[3], const int64_t v_strides[3], const void *bias,
