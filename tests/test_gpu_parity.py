@@ -411,6 +411,34 @@ def test_P_codes_round_to_nearest_with_scale_255():
     assert not np.allclose(got, trunc[None, :], rtol=2 ** -8, atol=0)
 
 
+def test_running_maximum_two_blocks_hand_worked():
+    # Alg. 1 worked by hand over two key blocks of the kernel (128 keys each).  Visible keys: key 0
+    # (first block, S = 0) and key 128 (second block, S = ln 4); everything else is masked.  The
+    # first block's P code is 255 relative to ITS maximum and the carry is multiplied by
+    # e^{0 - ln 4} = 1/4 when the second block raises the maximum (63.75, unrounded), where the
+    # global-maximum form would round 255 / 4 to the code 64.  V rows (1, -1/2): delta = 1/127,
+    # codes 127 and rne(-63.5) = -64; l = 1/4 + 1.
+    N, d = 129, 8
+    q = torch.ones(1, 1, N, d, dtype=torch.bfloat16)
+    k = torch.ones(1, 1, N, d, dtype=torch.bfloat16)
+    k[0, 0, 128] = -1.0
+    v = torch.zeros(1, 1, N, d, dtype=torch.bfloat16)
+    v[0, 0, 0], v[0, 0, 128] = 1.0, -0.5
+    bias = torch.full((1, N, N), float("-inf"), dtype=torch.float32)
+    bias[0, :, 0] = -1.0                       # S = 8/8 - 1
+    bias[0, :, 128] = 1.0 + math.log(4.0)      # S = -8/8 + 1 + ln 4
+    y_run = (63.75 * 127 - 255 * 64) / (255 * 1.25) / 127
+    y_glob = (64 * 127 - 255 * 64) / (255 * 1.25) / 127
+    for name, fn in (("three calls", lambda: ba.forward(*ba.pack_qk(dev(q), dev(k)), dev(v), dev(bias), 1.0 / d, flags=ba.FLAG_NO_MU)),
+                     ("one launch", lambda: ba.forward_fused(dev(q), dev(k), dev(v), dev(bias), 1.0 / d, flags=ba.FLAG_NO_MU))):
+        out = fn()
+        torch.cuda.synchronize()
+        got = gpu_out_f64(out)
+        say(f"    {name}: out {got.min():.6f} .. {got.max():.6f}, running-maximum value {y_run:.6f}, global-maximum value {y_glob:.6f}")
+        assert np.abs(got - y_run).max() <= 2 ** -9 * abs(y_run)          # bf16 rounding of the output
+        assert np.abs(got - y_glob).min() > 2 ** -9 * abs(y_glob)
+
+
 def test_masked_rows_via_minus_inf_bias_do_not_poison():
     # -inf bias on a whole leading key block (attention-mask style) must not produce NaN
     N, d = 260, 64

@@ -356,6 +356,34 @@ def test_algorithm1_quantised_single_block_equals_definition_and_blocks_stay_clo
     assert np.array_equal(sub, orc.algorithm1_rows(*args, Bv=32, quantise=True)[rows])
 
 
+def test_algorithm1_quantised_two_blocks_hand_worked_running_maximum():
+    # Alg. 1 with one key per block, worked by hand.  Two keys, logits S = (0, ln 4): the first
+    # block sees only S_1, so its P code is 255 relative to ITS maximum and the carry is later
+    # multiplied by e^{0 - ln 4} = 1/4 (unrounded: 63.75), while the global-maximum form rounds
+    # 255 / 4 = 63.75 to the code 64.  V = (1, -1/2) per channel: delta = 1/127, codes 127 and
+    # rne(-63.5) = -64.  l = 1/4 + 1.
+    #   running maximum: y = (63.75 * 127 - 255 * 64) / (255 * 1.25) / 127
+    #   global maximum : y = (64    * 127 - 255 * 64) / (255 * 1.25) / 127
+    d = 8
+    q = bf16_bits(torch.ones(2, d))                                        # two identical query rows
+    k = bf16_bits(torch.stack([torch.ones(d), -torch.ones(d)]))            # I = +8, -8
+    v = bf16_bits(torch.stack([torch.ones(d), -0.5 * torch.ones(d)]))
+    bias = np.array([[-1.0, 1.0 + math.log(4.0)]] * 2, dtype=np.float32)   # S = 8/8 - 1, -8/8 + 1 + ln 4
+    vq, delta = orc.quant_v(v)
+    assert np.all(vq[0] == 127) and np.all(vq[1] == -64) and np.all(delta == np.float32(1.0) / np.float32(127.0))
+    args = (q, np.ascontiguousarray(k), np.ascontiguousarray(v), bias, 1.0 / d, 1.0, 1.0, vq, delta)
+    run = orc.algorithm1_rows(*args, Bv=1, quantise=True)
+    glob = orc.attention_rows(*args, want=("O2",))["O2"]
+    dl = float(delta[0])
+    y_run = (63.75 * 127 - 255 * 64) / (255 * 1.25) * dl
+    y_glob = (64 * 127 - 255 * 64) / (255 * 1.25) * dl
+    assert abs(y_run - y_glob) > 5e-4                      # the two forms really differ here
+    assert np.allclose(run, y_run, rtol=0, atol=2e-7)      # (ln 4 as an fp32 bias: 1e-7 relative)
+    assert np.allclose(glob, y_glob, rtol=0, atol=2e-7)
+    # both keys in one block: Alg. 1 is the global-maximum form
+    assert np.allclose(orc.algorithm1_rows(*args, Bv=2, quantise=True), y_glob, rtol=0, atol=2e-7)
+
+
 @pytest.mark.parametrize("Bv", [8, 64, 1000])
 def test_algorithm1_masked_keys_equal_deleted_keys(Bv):
     # A -inf bias is a mask: the result must be the softmax attention (library routine) over
