@@ -44,3 +44,12 @@ def test_headline_kernels_have_the_expected_shape():
     assert pair["vgprs"] <= 256 and pair["scratch_bytes"] == 0 and 100 * 1024 <= pair["lds_bytes"] <= 128 * 1024
     dit = fv[(3, 5, 1, 0)]           # d = 72, private bias tiles, two workgroups per compute unit
     assert dit["scratch_bytes"] == 0 and dit["lds_bytes"] <= 80 * 1024
+
+
+def test_four_wave_single_launch_kernels_fit_two_per_compute_unit():
+    fv = fused_variants()
+    four = {k: r for k, r in fv.items() if k[3] == 3}   # WIDE_ONEHEAD4
+    assert len(four) >= 18
+    for key, r in sorted(four.items()):
+        assert key[2] == 1 and key[0] <= 3, key
+        assert r["scratch_bytes"] == 0 and r["lds_bytes"] <= 80 * 1024, (key, r)
