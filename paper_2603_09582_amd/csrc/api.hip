@@ -1,6 +1,5 @@
 // C ABI of libbinattn: argument validation (before anything is launched) and
 // the launch sequences.  See include/binattn.h for the contract.
-#include <cstdlib>
 #include "binattn_internal.h"
 
 #include <mutex>
