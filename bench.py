@@ -567,8 +567,13 @@ def main():
             "t_bound_ms": bd["t_bound_fused_ms"], "frac_of_t_bound": bd["t_bound_fused_ms"] / res["fused_ms"],
             "mfma_int8_frac": res["mfma_tops_algorithmic"] / MFMA_I8_PEAK_TOPS,
             "hbm_frac": res["fused_hbm_gbs"] / HBM_PEAK_GBS, "hbm_gbs": res["fused_hbm_gbs"]},
-        "clocks": {"rocm_smi_before_the_run": clocks, "ghz_under_a_v_fma_stream": clock_from_probe()},
+        "clocks": {"rocm_smi_before_the_run": clocks, "ghz_under_a_v_fma_stream": clock_from_probe(),
+                   "ghz_under_the_fused_kernel_rocm_smi": 2.18,
+                   "note": "the roofline peak assumes 2.4 GHz; rocm-smi --showclocks sampled during 1500 back-to-back "
+                           "steps of this workload read 2175-2195 MHz (profiles/binattn_kernels_vit_hires.txt)"},
     }
+    line["roofline"]["frac_at_the_clock_a_v_fma_stream_holds"] = (
+        line["roofline"]["frac"] * 2.4 / line["clocks"]["ghz_under_a_v_fma_stream"])
     del x
     torch.cuda.empty_cache()
     if not a.no_configs and not a.no_bias:
