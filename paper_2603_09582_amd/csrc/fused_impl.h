@@ -752,11 +752,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
             // The shared bias tile of the next block (BIAS_DB), one copy per tile of exponentials:
             // issued in one burst at the start of the block, beside the image copies, they fill
             // the memory pipeline's queue and hold the wave there (1.5 % of the block time).
-            if (BIAS_DB && more && t < 2 * RGW) {
-                __builtin_amdgcn_sched_barrier(0);
-                dma_bias_one(nsrc, nblkidx, bnxt, t);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            if (BIAS_DB && more && t < 2 * RGW) dma_bias_one(nsrc, nblkidx, bnxt, t);
         }
         }
         l_run = fmaf(l_run, resc, ls0 + ls1);
