@@ -309,6 +309,19 @@ def config_row(name, steps=CONFIG_STEPS, warmup=CONFIG_WARMUP):
             row["single_launch"]["ms_per_step_8_wave_form"] = med_min(per8)
         else:
             row["single_launch"]["workgroups"] = "8 waves, one per head"
+    if w.N % 8:       # the same bias in rows padded to a multiple of 8 elements: tiles staged through LDS
+        import torch
+        pitch = (w.N + 7) // 8 * 8
+        store = torch.zeros(w.H, w.N, pitch, dtype=x.bias.dtype, device=x.bias.device)
+        store[:, :, :w.N] = x.bias
+        pb = store[:, :, :w.N]
+        ev = lambda f: med_min(timed(f, steps, warmup)[1])
+        row["bias_rows_padded_to_8_elements"] = {
+            "row_pitch": pitch,
+            "attend_ms": ev(lambda i: ba.attend(b.q_bits, b.mu_q, b.mu_k, pb, x.scale, w.d, b.ws, out=b.out)),
+            "single_launch_ms": ev(lambda i: ba.forward_fused(x.q, x.k, x.v, pb, x.scale, out=b.out)),
+            "note": "not the headline layout: the configuration's bias is [H, N, N] contiguous, read row by row into registers"}
+        del store, pb
     # the fastest way through the library for this configuration, against that path's own bound
     cands = [("pack_qk + prepare_kv + attend", row["ms_per_step"]["median"], row["step_frac_of_bound"])]
     if "one_call" in row:

@@ -130,7 +130,11 @@ int binattn_prepare_kv(const uint32_t *k_bits, const void *v, const int64_t v_st
  *                the batch.  May be NULL (no bias).  Rows need only element
  *                alignment; the fastest path (tiles staged through LDS) needs
  *                bf16, a 16-byte aligned base, strides that keep every row
- *                16-byte aligned and N a multiple of 8 (and N > 128 if d > 96).
+ *                16-byte aligned, and either N a multiple of 8 or a row stride of
+ *                at least N rounded up to a multiple of 8 (e.g. N = 197 in rows
+ *                of 200 elements: the padding elements of every row, the last
+ *                one included, are then read - they must be inside the
+ *                allocation - and ignored); and N > 128 if d > 96.
  *   scale      : multiplies the +-1 inner product (1/sqrt(d) in Eq. 6); the
  *                effective multiplier is scale * mu_q[b,h] * mu_k[b,h].
  *   out        : bf16 [B, H, N, d], strides out_strides, rounded to nearest even

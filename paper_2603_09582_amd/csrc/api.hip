@@ -208,7 +208,8 @@ int attend_impl(const uint32_t *q_bits, const float *mu_q, const float *mu_k, co
             const bool rows16 = aligned(bias, 16) && bs.b % 8 == 0 && bs.h % 8 == 0 && bs.n % 8 == 0;
             // (and a row pitch whose 7-fold fits a 32-bit lane offset)
             // (d > 96 and at least two row blocks: 8-wave workgroups over row-block pairs)
-            const bool lds_ok = rows16 && N % 8 == 0 && bs.n < (1 << 27);
+            // (N no multiple of 8: the chunk that straddles the row end must lie inside the row pitch)
+            const bool lds_ok = rows16 && (N % 8 == 0 || bs.n >= (N + 7) / 8 * 8) && bs.n < (1 << 27);
             wide_rows2 = lds_ok && s.DK == 4 && N > BR && raw == nullptr;
             mode = (lds_ok && (s.DK <= 3 || wide_rows2)) ? BIAS_BF16_LDS : BIAS_BF16_VEC;
         } else {

@@ -393,7 +393,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
 #pragma unroll
             for (int gh = 0; gh < 2; ++gh) {
                 const int key0 = blk * BV + 64 * gh + 8 * dma_c[j];
-                if (key0 + 8 <= N)
+                if (key0 < N)  // (a last chunk that straddles N lies inside the row pitch: the host checked)
                     dma16(src.base[j] + (blk * BV + 64 * gh) * 2, src.voff[j],
                           region + ((rg0 + j) * 2 + gh) * 1024);
             }
@@ -401,7 +401,7 @@ __global__ __launch_bounds__(FUSED_THREADS * NB, 2) void fused_kernel(const Fuse
     auto dma_bias_one = [&](const BiasSrc &src, int blk, unsigned region, int idx) {  // copy idx = 2 j + gh of dma_bias
         const int j = idx >> 1, gh = idx & 1;
         const int key0 = blk * BV + 64 * gh + 8 * dma_c[j];
-        if (key0 + 8 <= N)
+        if (key0 < N)
             dma16(src.base[j] + (blk * BV + 64 * gh) * 2, src.voff[j], region + ((rg0 + j) * 2 + gh) * 1024);
     };
     u4v braw[8];  // the 64 bf16 bias values of this lane for the current block

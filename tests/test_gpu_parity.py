@@ -233,17 +233,29 @@ def test_forward_matches_oracle_bf16_bias(B, H, N, d):
     assert np.all(err <= 2e-3 + 2 ** -7 * np.abs(alg))
 
 
-def test_forward_bf16_bias_padded_rows_odd_n():
-    # N = 197 inside rows padded to 200 elements: 16-byte aligned rows but a ragged row end,
-    # which takes the register-prefetch bias path with its guarded last chunk
-    B, H, N, d = 1, 2, 197, 64
-    x = small_inputs(B, H, N, d, 55)
-    store = torch.zeros(H, N, 200, dtype=torch.bfloat16, device="cuda")
+@pytest.mark.parametrize("B,H,N,d,pitch", [(1, 2, 197, 64, 200), (2, 2, 197, 72, 208), (1, 1, 129, 32, 136),
+                                           (2, 1, 1001, 64, 1008), (1, 2, 255, 96, 256), (1, 1, 300, 128, 304),
+                                           (1, 300, 197, 64, 200)])
+def test_forward_bf16_bias_padded_rows_odd_n(B, H, N, d, pitch):
+    # N no multiple of 8 inside rows padded to a multiple of 8 elements: 16-byte aligned rows whose
+    # last 16-byte chunk straddles the row end but lies inside the row pitch: the LDS-staged bias
+    # path, with the padding elements (poisoned here) read and ignored.  All three ways in.
+    say(f"padded odd-N bias rows B={B} H={H} N={N} d={d} pitch={pitch}")
+    x = small_inputs(B, H, N, d, 55 + N)
+    store = torch.full((H, N, pitch), float("nan"), dtype=torch.bfloat16, device="cuda")
     store[:, :, :N] = dev(x.bias)
-    qb, kb, mq, mk = ba.pack_qk(dev(x.q), dev(x.k))
-    out = ba.forward(qb, kb, mq, mk, dev(x.v), store[:, :, :N], x.scale)
+    bias = store[:, :, :N]
+    ref = oracle_forward(x, x.bias)["O2"]
+    q, k, v = dev(x.q), dev(x.k), dev(x.v)
+    qb, kb, mq, mk = ba.pack_qk(q, k)
+    outs = {"three calls": ba.forward(qb, kb, mq, mk, v, bias, x.scale), "one call": ba.attention(q, k, v, bias, x.scale)}
+    if N <= 256:
+        outs["one launch"] = ba.forward_fused(q, k, v, bias, x.scale)
     torch.cuda.synchronize()
-    check_close(gpu_out_f64(out), oracle_forward(x, x.bias)["O2"], "padded odd-N rows: out vs O2")
+    for name, out in outs.items():
+        got = gpu_out_f64(out)
+        assert np.isfinite(got).all(), name
+        check_close(got, ref, f"padded odd-N rows, {name}: out vs O2")
 
 
 @pytest.mark.parametrize("kind", ["none", "f32", "f32_per_batch", "bf16_per_batch", "bf16_padded_rows",
