@@ -725,6 +725,42 @@ def test_hip_graph_replay_of_the_one_call_path_is_bit_identical():
     check_close(gpu_out_f64(out)[:, :, ::37], ref, "graph test (one call), last inputs vs O2")
 
 
+def test_concurrent_calls_on_two_streams_do_not_interfere():
+    # The library keeps no state between calls (the static buffer of binattn_forward_static aside):
+    # two problems of different shape, each on a stream of its own, every entry point, issued
+    # alternately so that their kernels overlap on the chip; results equal those of the same calls
+    # made one after the other.
+    xa = small_inputs(2, 2, 700, 64, 31)
+    xb = small_inputs(1, 3, 200, 72, 32)
+    A = [dev(t) for t in (xa.q, xa.k, xa.v, xa.bias)]
+    Bt = [dev(t) for t in (xb.q, xb.k, xb.v, xb.bias)]
+
+    def run_a():
+        qb, kb, mq, mk = ba.pack_qk(A[0], A[1])
+        return ba.forward(qb, kb, mq, mk, A[2], A[3], xa.scale), ba.attention(A[0], A[1], A[2], A[3], xa.scale)
+
+    def run_b():
+        qb, kb, mq, mk = ba.pack_qk(Bt[0], Bt[1])
+        return ba.forward(qb, kb, mq, mk, Bt[2], Bt[3], xb.scale), ba.forward_fused(Bt[0], Bt[1], Bt[2], Bt[3], xb.scale)
+
+    ref_a, ref_b = run_a(), run_b()
+    torch.cuda.synchronize()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    outs_a, outs_b = [], []
+    for _ in range(6):
+        with torch.cuda.stream(sa):
+            outs_a.append(run_a())
+        with torch.cuda.stream(sb):
+            outs_b.append(run_b())
+    torch.cuda.synchronize()
+    for got in outs_a:
+        assert all(torch.equal(g, r) for g, r in zip(got, ref_a))
+    for got in outs_b:
+        assert all(torch.equal(g, r) for g, r in zip(got, ref_b))
+    check_close(gpu_out_f64(ref_a[0]), oracle_forward(xa, xa.bias)["O2"], "two streams, problem A vs O2")
+    check_close(gpu_out_f64(ref_b[1]), oracle_forward(xb, xb.bias)["O2"], "two streams, problem B vs O2")
+
+
 # ---- the single-launch form for short sequences -------------------------------------------
 FUSED_SHAPES = [(1, 2, 1, 64), (1, 2, 2, 8), (2, 1, 63, 64), (1, 2, 64, 72), (1, 1, 65, 128), (1, 3, 129, 64),
                 (2, 2, 197, 64), (1, 2, 255, 72), (3, 2, 256, 72), (1, 1, 256, 128), (1, 2, 136, 96),
