@@ -275,6 +275,19 @@ int binattn_forward_fused_relpos(const void *q, const void *k, const void *v, co
                                  unsigned flags, void *stream);
 
 /*
+ * binattn_attention with the relative-position table of binattn_attend_relpos as bias (the
+ * bias trained in Sec. 5.6), for any N = Gy * Gx within that call's grid limits: one launch
+ * where binattn_forward_fused_relpos applies, else the three launches of binattn_attention.
+ * No [N, N] bias exists anywhere.  Arguments as binattn_forward_fused_relpos plus the
+ * workspace of binattn_workspace_bytes (unused and may be NULL in the one-launch case).
+ */
+int binattn_attention_relpos(const void *q, const void *k, const void *v, const int64_t q_strides[3],
+                             const int64_t k_strides[3], const int64_t v_strides[3], const float *table, int Gy,
+                             int Gx, float scale, int B, int H, int N, int d, void *out,
+                             const int64_t out_strides[3], float *mu_q_out, float *mu_k_out, void *workspace,
+                             size_t workspace_bytes, unsigned flags, void *stream);
+
+/*
  * Integer logits I_ij = s_i . t_j of Sec. 4.1 for query rows
  * [row_begin, row_end) of every head: int32 [B, H, row_end - row_begin, N]
  * contiguous.  BINATTN_LOGITS_MFMA_FP4 runs the same tile routine as the fused

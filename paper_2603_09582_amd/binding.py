@@ -23,7 +23,7 @@ LOGITS_ROWSUM = 0x100
 EXPORTS = ["binattn_version", "binattn_strerror", "binattn_pack_qk", "binattn_workspace_bytes",
            "binattn_prepare_kv", "binattn_attend", "binattn_forward", "binattn_attend_axial",
            "binattn_forward_axial", "binattn_attend_relpos", "binattn_forward_relpos", "binattn_forward_fused",
-           "binattn_forward_fused_relpos", "binattn_forward_static", "binattn_probe_valu", "binattn_attention",
+           "binattn_forward_fused_relpos", "binattn_forward_static", "binattn_probe_valu", "binattn_attention", "binattn_attention_relpos",
            "binattn_logits_debug", "binattn_quant_v_debug"]
 
 _lib = None
@@ -93,6 +93,10 @@ def lib():
     L.binattn_forward_fused_relpos.restype = C.c_int
     L.binattn_forward_fused_relpos.argtypes = [vp, vp, vp, i64p, i64p, i64p, vp, C.c_int, C.c_int, C.c_float,
                                                C.c_int, C.c_int, C.c_int, C.c_int, vp, i64p, vp, vp, C.c_uint, vp]
+    L.binattn_attention_relpos.restype = C.c_int
+    L.binattn_attention_relpos.argtypes = [vp, vp, vp, i64p, i64p, i64p, vp, C.c_int, C.c_int, C.c_float,
+                                           C.c_int, C.c_int, C.c_int, C.c_int, vp, i64p, vp, vp, vp, C.c_size_t,
+                                           C.c_uint, vp]
     L.binattn_logits_debug.restype = C.c_int
     L.binattn_logits_debug.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                        vp, C.c_int, vp, C.c_size_t, vp]
@@ -349,6 +353,26 @@ def attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, bias: Optional[
         None if workspace is None else workspace.data_ptr(), 0 if workspace is None else workspace.numel(),
         int(flags), _stream())
     _check(rc, "binattn_attention")
+    return out
+
+
+def attention_relpos(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, table: torch.Tensor, scale: float,
+                     out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                     mu_q: Optional[torch.Tensor] = None, mu_k: Optional[torch.Tensor] = None, flags: int = 0) -> torch.Tensor:
+    """binattn_attention_relpos: the forward pass from the bf16 tensors with the head's relative-position table, any N."""
+    assert q.dtype == k.dtype == v.dtype == torch.bfloat16 and q.is_cuda
+    B, H, N, d = q.shape
+    Gy, Gx = _relpos_table(table, H)
+    if out is None:
+        out = torch.empty(B, H, N, d, dtype=torch.bfloat16, device=q.device)
+    if workspace is None:
+        workspace = alloc_workspace(B, H, N, d, q.device)
+    rc = lib().binattn_attention_relpos(
+        q.data_ptr(), k.data_ptr(), v.data_ptr(), _strides3(q), _strides3(k), _strides3(v), table.data_ptr(),
+        Gy, Gx, float(scale), B, H, N, d, out.data_ptr(), _strides3(out),
+        None if mu_q is None else mu_q.data_ptr(), None if mu_k is None else mu_k.data_ptr(),
+        workspace.data_ptr(), workspace.numel(), int(flags), _stream())
+    _check(rc, "binattn_attention_relpos")
     return out
 
 

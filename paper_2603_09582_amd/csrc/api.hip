@@ -495,6 +495,40 @@ int binattn_forward_fused_relpos(const void *q, const void *k, const void *v, co
                        out_strides, nullptr, 0, flags, stream);
 }
 
+int binattn_attention_relpos(const void *q, const void *k, const void *v, const int64_t q_strides[3],
+                             const int64_t k_strides[3], const int64_t v_strides[3], const float *table, int Gy,
+                             int Gx, float scale, int B, int H, int N, int d, void *out,
+                             const int64_t out_strides[3], float *mu_q_out, float *mu_k_out, void *workspace,
+                             size_t workspace_bytes, unsigned flags, void *stream) {
+    if (!table) return BINATTN_ERR_NULL;
+    if (N <= 2 * BV && Gx <= TABLE_MAX_G && Gy <= TABLE_MAX_G)  // the single launch holds the whole table in LDS
+        return binattn_forward_fused_relpos(q, k, v, q_strides, k_strides, v_strides, table, Gy, Gx, scale, B, H, N, d,
+                                            out, out_strides, mu_q_out, mu_k_out, flags, stream);
+    if (!q || !k || !v || !out) return BINATTN_ERR_NULL;
+    if (!shape_ok(B, H, N, d)) return BINATTN_ERR_SHAPE;
+    const Shape s = make_shape(B, H, N, d);
+    const Workspace w = make_workspace(s);
+    Strides3 qs, ks, vs, os;
+    int rc;
+    if ((rc = check_strides_bhnd(q_strides, s, &qs)) != BINATTN_OK) return rc;
+    if ((rc = check_strides_bhnd(k_strides, s, &ks)) != BINATTN_OK) return rc;
+    if ((rc = check_strides_bhnd(v_strides, s, &vs)) != BINATTN_OK) return rc;
+    if ((rc = check_strides_bhnd(out_strides, s, &os)) != BINATTN_OK) return rc;
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16)) return BINATTN_ERR_ALIGN;
+    if ((mu_q_out && !aligned(mu_q_out, 4)) || (mu_k_out && !aligned(mu_k_out, 4))) return BINATTN_ERR_ALIGN;
+    AxialBias ax = {nullptr, nullptr, Gy, Gx};
+    ax.table = table;
+    if ((rc = check_axial(ax, N, false)) != BINATTN_OK) return rc;
+    if ((rc = check_workspace(workspace, workspace_bytes, w)) != BINATTN_OK) return rc;
+    char *ws = static_cast<char *>(workspace);
+    if ((rc = launch_phi_psi(q, qs, k, ks, v, vs, s, ws, w, mu_q_out, mu_k_out, static_cast<hipStream_t>(stream))) !=
+        BINATTN_OK)
+        return rc;
+    const float *mu = reinterpret_cast<const float *>(ws + w.mu);
+    return binattn_attend_relpos(reinterpret_cast<const uint32_t *>(ws + w.qbits), mu, mu + s.BH, table, Gy, Gx, scale,
+                                 B, H, N, d, out, out_strides, workspace, workspace_bytes, flags, stream);
+}
+
 int binattn_logits_debug(const uint32_t *q_bits, const uint32_t *k_bits, int B, int H, int N, int d,
                          int row_begin, int row_end, int32_t *logits, int variant, void *workspace,
                          size_t workspace_bytes, void *stream) {

@@ -167,6 +167,24 @@ def test_forward_fused_relpos_rejects_bad_arguments():
     assert fused_relpos(table=FAKE + 2) == -4 and fused_relpos(v=FAKE + 8) == -4 and fused_relpos(mq=FAKE + 1) == -4
 
 
+def attention_relpos(q=FAKE, v=FAKE, out=FAKE, table=FAKE, Gy=32, Gx=64, N=2048, d=64, mq=FAKE, ws=FAKE, wsb=1 << 30):
+    B, H = 2, 2
+    s3 = st(H * N * d, N * d, d)
+    return ba.lib().binattn_attention_relpos(q, FAKE, v, s3, s3, s3, table, Gy, Gx, 0.125, B, H, N, d, out, s3,
+                                             mq, None, ws, wsb, 0, None)
+
+
+def test_attention_relpos_rejects_bad_arguments():
+    assert attention_relpos(table=None) == -1 and attention_relpos(q=None) == -1 and attention_relpos(out=None) == -1
+    assert attention_relpos(Gy=31) == -2 and attention_relpos(Gx=48, Gy=32, N=1536) == -2   # N = Gy Gx, Gx a power of two
+    assert attention_relpos(d=60) == -2
+    assert attention_relpos(table=FAKE + 2) == -4 and attention_relpos(v=FAKE + 8) == -4 and attention_relpos(mq=FAKE + 1) == -4
+    assert attention_relpos(ws=None) == -5 and attention_relpos(wsb=64) == -5
+    # a grid the single launch takes: its checks apply
+    assert attention_relpos(Gy=16, Gx=16, N=256, table=None) == -1
+    assert attention_relpos(Gy=16, Gx=16, N=256, q=None) == -1
+
+
 def test_debug_entry_points_reject_bad_arguments():
     L = ba.lib()
     f = lambda **k: L.binattn_logits_debug(

@@ -139,12 +139,12 @@ def draw_grid_case(seed):
             B -= 1
         else:
             H -= 1
-    forms = ["axial", "table"] + (["table_fused"] if N <= 256 and Gx <= 32 and Gy <= 32 else [])
+    forms = ["axial", "table", "table_one_call"] + (["table_fused"] if N <= 256 and Gx <= 32 and Gy <= 32 else [])
     form = "table_fused" if seed % 4 == 0 else forms[int(rng.integers(0, len(forms)))]
     return dict(B=B, H=H, Gy=Gy, Gx=Gx, d=d, form=form, amp=[0.3, 0.7, 2.0][int(rng.integers(0, 3))])
 
 
-@pytest.mark.parametrize("seed", range(40))
+@pytest.mark.parametrize("seed", range(56))
 def test_random_grid_bias_matches_dense_oracle(seed):
     from tests.test_gpu_parity import axial_dense, relpos_dense
     c = draw_grid_case(seed)
@@ -165,6 +165,8 @@ def test_random_grid_bias_matches_dense_oracle(seed):
         dense = relpos_dense(table, Gy, Gx)
         if c["form"] == "table_fused":
             out = ba.forward_fused_relpos(q, k, v, dev(table), x.scale)
+        elif c["form"] == "table_one_call":
+            out = ba.attention_relpos(q, k, v, dev(table), x.scale)
         else:
             qb, kb, mq, mk = ba.pack_qk(q, k)
             out = ba.forward_relpos(qb, kb, mq, mk, v, dev(table), x.scale)
