@@ -630,6 +630,25 @@ def main():
         rows[0]["single_launch_ms_per_step"] = one_ms
         rows[0]["single_launch_tops_equiv"] = w256.equiv_ops / (one_ms * 1e-3) / 1e12
         del x256, o256
+        # ... and from the bf16 tensors behind one call (binattn_attention_relpos), any N
+        for row in rows:
+            w = wl.WORKLOADS[row["workload"]]
+            xw = wl.make_inputs(w, device="cuda", with_bias=False)
+            Gy, Gx = relpos_grid(w.N)
+            tb = torch.randn(w.H, 2 * Gy - 1, 2 * Gx - 1, generator=gen, device="cuda") * 0.02
+            ow = torch.empty_like(xw.q)
+            wsb = ba.alloc_workspace(w.B, w.H, w.N, w.d)
+            for _ in range(a.warmup):
+                ba.attention_relpos(xw.q, xw.k, xw.v, tb, xw.scale, out=ow, workspace=wsb)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                ba.attention_relpos(xw.q, xw.k, xw.v, tb, xw.scale, out=ow, workspace=wsb)
+            e1.record()
+            torch.cuda.synchronize()
+            row["one_call_ms_per_step"] = e0.elapsed_time(e1) / n
+            del xw, ow, wsb, tb
+            torch.cuda.empty_cache()
         line["relpos_table_bias"] = {"note": "b_ij = table[iy-jy][ix-jx], fp32 table rows staged in LDS",
                                      "workloads": rows}
     if a.sweep:
